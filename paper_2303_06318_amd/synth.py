@@ -1,0 +1,149 @@
+"""Seeded synthetic inputs for one MoE layer (tokens, gate weight, expert weights, upstream grad).
+
+This module only draws random numbers and rounds them to the storage type; it
+holds none of the layer's arithmetic.  Both the HIP path's tests and the CPU
+oracle's tests take their inputs from here so that they see identical arrays.
+
+Draw recipe
+-----------
+Every tensor is drawn from its own counter-based stream
+``Philox(key = seed * 2**32 + tensor_id * 2**16 + chunk)``, where ``chunk`` is
+the expert index for per-expert weights and a 0-based 4096-row block index for
+token-shaped tensors.  Values are ``standard_normal(float32) * std``.  For the
+bf16 workloads the fp32 draw is rounded to the nearest bf16 (ties to even) and
+returned both as the uint16 bit pattern (what the GPU stores) and as the fp32
+array holding exactly those values (what a CPU checker reads).
+
+The five named workloads follow the shapes of the paper's models (Table 1:
+hidden sizes 2048 and 4096, sequence length 2048; the FFN is four times the
+hidden size because two thirds of a base model's parameters sit in FFN blocks,
+Section 3.1; a tensor-parallel group of 4 for the 6.7B base, Section 7.4).
+"""
+from __future__ import annotations
+
+import math
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass, field
+
+import numpy as np
+
+TENSOR_X, TENSOR_WG, TENSOR_W1, TENSOR_W2, TENSOR_DOUT = 0, 1, 2, 3, 4
+_ROW_BLOCK = 4096
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    T: int
+    h: int
+    E: int
+    f: int
+    capacity_factor: float
+    dtype: str            # "f32" or "bf16" (storage type of x, w1, w2, d_out)
+    seed: int
+    x_std: float
+    w_std: float
+    wg_std: float
+    zipf_bias: bool = False
+    backward: bool = False
+
+    @property
+    def C(self) -> int:
+        return int(math.ceil(float(self.capacity_factor) * float(self.T) / float(self.E)))
+
+
+WORKLOADS = {
+    "cfg1_tiny_f32": Workload("cfg1_tiny_f32", 256, 64, 4, 256, 1.0, "f32", 0, 0.02, 0.02, 1.0),
+    "cfg2_1p3b_fwd": Workload("cfg2_1p3b_fwd", 8192, 2048, 16, 8192, 1.25, "bf16", 1, 1.0, 0.02, 0.02),
+    "cfg3_6p7b_tp4_fwd": Workload("cfg3_6p7b_tp4_fwd", 16384, 4096, 16, 4096, 1.25, "bf16", 2, 1.0, 0.02, 0.02),
+    "cfg4_skewed_fwd": Workload("cfg4_skewed_fwd", 16384, 2048, 64, 4096, 1.0, "bf16", 3, 1.0, 0.02, 0.02,
+                                zipf_bias=True),
+    "cfg5_6p7b_tp4_fwdbwd": Workload("cfg5_6p7b_tp4_fwdbwd", 16384, 4096, 16, 4096, 1.25, "bf16", 4, 1.0, 0.02,
+                                     0.02, backward=True),
+}
+
+
+def round_to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """fp32 array -> uint16 bf16 bit patterns, round to nearest, ties to even (finite inputs)."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    r = u + np.uint32(0x7FFF) + lsb
+    return (r >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def _draw(seed: int, tensor_id: int, chunk: int, shape, std: float) -> np.ndarray:
+    key = (int(seed) << 32) + (int(tensor_id) << 16) + int(chunk)
+    g = np.random.Generator(np.random.Philox(key=key))
+    a = g.standard_normal(shape, dtype=np.float32)
+    if std != 1.0:
+        a *= np.float32(std)
+    return a
+
+
+def _draw_chunks(seed, tensor_id, n_chunks, chunk_shape_of, std, threads):
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        parts = list(ex.map(lambda c: _draw(seed, tensor_id, c, chunk_shape_of(c), std), range(n_chunks)))
+    return parts
+
+
+def _token_tensor(seed, tensor_id, T, h, std, threads):
+    n_chunks = (T + _ROW_BLOCK - 1) // _ROW_BLOCK
+    parts = _draw_chunks(seed, tensor_id, n_chunks,
+                         lambda c: (min(_ROW_BLOCK, T - c * _ROW_BLOCK), h), std, threads)
+    return np.concatenate(parts, axis=0) if parts else np.zeros((0, h), np.float32)
+
+
+@dataclass
+class LayerInputs:
+    wl: Workload
+    # fp32 arrays holding exactly the stored values (bf16-representable for bf16 workloads)
+    x: np.ndarray
+    wg: np.ndarray
+    w1: np.ndarray
+    w2: np.ndarray
+    d_out: np.ndarray | None
+    logit_bias: np.ndarray | None      # [E] fp32 added to the gate logits (skewed workload), else None
+    bits: dict = field(default_factory=dict)   # name -> uint16 bf16 patterns (bf16 workloads only)
+
+
+def zipf_logit_bias(E: int) -> np.ndarray:
+    """Per-expert additive logit offset 2*ln(1/(e+1)) for 0-based expert e, in fp32."""
+    e = np.arange(E, dtype=np.float64)
+    return (2.0 * np.log(1.0 / (e + 1.0))).astype(np.float32)
+
+
+def make_inputs(wl: Workload, *, experts: int | None = None, threads: int = 8,
+                need_bits: bool = True) -> LayerInputs:
+    """Draw the layer's inputs.  ``experts`` limits how many experts' weights are drawn
+    (the first ``experts`` ones; their values do not depend on the limit)."""
+    nE = wl.E if experts is None else int(experts)
+    x = _token_tensor(wl.seed, TENSOR_X, wl.T, wl.h, wl.x_std, threads)
+    wg = _draw(wl.seed, TENSOR_WG, 0, (wl.h, wl.E), wl.wg_std)
+    w1 = np.stack(_draw_chunks(wl.seed, TENSOR_W1, nE, lambda e: (wl.h, wl.f), wl.w_std, threads)) \
+        if nE else np.zeros((0, wl.h, wl.f), np.float32)
+    w2 = np.stack(_draw_chunks(wl.seed, TENSOR_W2, nE, lambda e: (wl.f, wl.h), wl.w_std, threads)) \
+        if nE else np.zeros((0, wl.f, wl.h), np.float32)
+    d_out = _token_tensor(wl.seed, TENSOR_DOUT, wl.T, wl.h, 1.0, threads) if wl.backward else None
+    bits = {}
+    if wl.dtype == "bf16":
+        for name in ("x", "w1", "w2", "d_out"):
+            a = {"x": x, "w1": w1, "w2": w2, "d_out": d_out}[name]
+            if a is None:
+                continue
+            b = round_to_bf16_bits(a)
+            a[...] = bf16_bits_to_f32(b)
+            if need_bits:
+                bits[name] = b
+    bias = zipf_logit_bias(wl.E) if wl.zipf_bias else None
+    return LayerInputs(wl, x, wg, w1, w2, d_out, bias, bits)
+
+
+def scaled(wl: Workload, **kw) -> Workload:
+    """A copy of a workload with some fields replaced (used for reduced-size parity cases)."""
+    d = dict(wl.__dict__)
+    d.update(kw)
+    return Workload(**d)
