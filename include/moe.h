@@ -1,0 +1,185 @@
+/*
+ * moe.h -- C ABI of the MI355X (gfx950) library for one GPU's share of a TED
+ * Mixture-of-Experts layer: top-1 gate, capacity-limited routing, dispatch into
+ * per-expert buffers, the per-expert FFN shard (GEMM, GeLU, GEMM), the
+ * gate-weighted combine, and the backward of all of these.
+ *
+ * Paper: "A Hybrid Tensor-Expert-Data Parallelism Approach to Optimize
+ * Mixture-of-Experts Training" (DeepSpeed-TED).  The layer is Section 1 /
+ * Figure 1 (a routing function sends each token to exactly one expert FFN);
+ * the per-GPU order of work is Section 3, Figure 3, steps 3 (routing), 4 (tokens
+ * leave for their expert), 5 (expert FFN, one tensor-parallel partition), 7
+ * (tokens return); the backward runs the same steps in reverse (end of
+ * Section 3).  This library is the local computation between the collectives:
+ * steps 2, 4, 6 and 7's communication is not part of it, so the FFN output is
+ * the partial sum of this GPU's f inner columns.
+ *
+ * Notation: T tokens, h hidden size, E experts, f FFN inner width owned by this
+ * GPU (4h / G_tensor), C capacity (rows per expert buffer), e_t / s_t / p_t the
+ * expert, slot and gate probability of token t, kept_e = min(count_e, C).
+ *
+ * Conventions for every entry point
+ *  - All array arguments are DEVICE pointers (HBM) unless marked "host".
+ *    All arrays are dense, row-major, with the index order written next to them,
+ *    and must be 16-byte aligned.  The caller owns every buffer; the library
+ *    never allocates, frees or keeps a pointer after the call returns.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *    only enqueue work on it; there is no host synchronisation and no host read
+ *    of device data (kept_e is read on the device, so launches cover C rows per
+ *    expert and skip the unused part).
+ *  - `dtype` is the storage type of x, buffers, expert weights and their
+ *    gradients: MOE_BF16 (fp32 accumulation on MFMA) or MOE_F32.  The gate
+ *    (w_gate, logits, probs, gate_p and their gradients) is always fp32.
+ *  - Returns MOE_OK or an error code; never throws or aborts.  Arguments are
+ *    validated on the host before anything is launched: a failed call launches
+ *    nothing.  moe_last_error() gives a thread-local description.
+ *  - Not checked (undefined results, no memory fault as long as the arrays have
+ *    the stated sizes and expert/slot came from moe_gate): non-finite logits.
+ *  - Limits: 1 <= E <= 256; h and f multiples of 8 (bf16) or 4 (fp32);
+ *    T, C >= 1; E*C*max(h,f) < 2^40; C*max(h,f)*sizeof(dtype) < 2^31.
+ */
+#ifndef MOE_TED_H
+#define MOE_TED_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_ERR_INVALID_ARG = 1,        /* null pointer, non-positive size, misaligned pointer */
+    MOE_ERR_UNSUPPORTED = 2,        /* size outside the limits above, unknown dtype/act */
+    MOE_ERR_WORKSPACE_TOO_SMALL = 3,
+    MOE_ERR_HIP = 4                 /* a HIP launch reported an error */
+} moe_status_t;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype_t;
+typedef enum { MOE_GELU_ERF = 0, MOE_GELU_TANH = 1 } moe_act_t;
+
+typedef struct {
+    int64_t T;      /* tokens on this GPU */
+    int32_t h;      /* hidden size */
+    int32_t E;      /* experts */
+    int32_t f;      /* FFN inner width of this tensor-parallel shard */
+    int64_t C;      /* capacity: rows per expert buffer */
+    int32_t dtype;  /* moe_dtype_t */
+    int32_t act;    /* moe_act_t */
+} moe_shape_t;
+
+/* Host helpers (pure, no GPU needed). */
+
+/* C = ceil(capacity_factor * T / E) evaluated in double; 0 on bad arguments. */
+int64_t moe_capacity(int64_t T, int32_t E, double capacity_factor);
+
+/* Bytes of device workspace the calls below need for this shape (one workspace serves
+ * all calls of a layer; contents need not survive between calls except as noted).
+ * 0 on a bad shape. */
+size_t moe_workspace_bytes(const moe_shape_t *shape, int for_backward);
+
+const char *moe_status_string(moe_status_t s);
+const char *moe_last_error(void);   /* thread-local text of the last failure in this thread */
+int moe_version(void);
+
+/*
+ * Gate + routing (Section 3, step 3: "each GPU applies the MoE routing function to its local
+ * tokens"; Section 1: the function is parameterised and maps each token to exactly one expert).
+ *   logits[t,j] = sum_k x[t,k] w_gate[k,j]  (+ logit_bias[j])      fp32
+ *   e_t   = lowest j attaining max_j logits[t,j]
+ *   probs = softmax_j(logits[t,:]),  p_t = probs[t,e_t]
+ *   s_t   = #{u < t : e_u = e_t};  slot[t] = s_t if s_t < C else -1 (dropped)
+ *   counts[e] = #{t : e_t = e} (before dropping);  kept[e] = min(counts[e], C)
+ *   token_of_slot[e,s] = the token holding slot s of expert e, -1 if the slot is empty
+ * x == NULL: `logits` is an input (already biased) and w_gate / logit_bias are ignored;
+ * otherwise `logits` is an output.  probs may be NULL when no backward follows.
+ *   x [T,h] dtype, w_gate [h,E] f32, logit_bias [E] f32 or NULL, logits [T,E] f32,
+ *   probs [T,E] f32 or NULL, expert [T] i32, gate_p [T] f32, slot [T] i32,
+ *   counts [E] i32, kept [E] i32, token_of_slot [E,C] i32.
+ * Routing outputs are integers and are reproducible bit for bit (no dependence on
+ * atomic ordering).
+ */
+moe_status_t moe_gate(const moe_shape_t *shape, const void *x, const float *w_gate, const float *logit_bias,
+                      float *logits, float *probs, int32_t *expert, float *gate_p, int32_t *slot,
+                      int32_t *counts, int32_t *kept, int32_t *token_of_slot, void *ws, size_t ws_bytes,
+                      void *stream);
+
+/*
+ * Dispatch (Section 3, step 4, local half: tokens are grouped by destination expert into
+ * equal-size chunks, which is the send layout of the all-to-all).
+ *   buf[e,s,:] = x[token_of_slot[e,s],:]  for filled slots, 0 for empty ones.
+ *   x [T,h], token_of_slot [E,C], buf [E,C,h].
+ */
+moe_status_t moe_dispatch(const moe_shape_t *shape, const void *x, const int32_t *token_of_slot, void *buf,
+                          void *stream);
+
+/*
+ * Expert FFN forward (Section 3, step 5; Section 2.4: a pair of consecutive fully connected
+ * layers, of which this GPU holds f inner columns of the first and the matching f rows of the
+ * second, so y is a partial sum that step 6's all-reduce would complete).
+ *   for r < kept[e]:  z = buf[e,r,:] w1[e] ;  hact = GeLU(z) ;  y[e,r,:] = hact w2[e]
+ * Rows r >= kept[e] of hact, z_save and y are not written.
+ *   buf [E,C,h], w1 [E,h,f], w2 [E,f,h], kept [E], hact [E,C,f] (out, needed by backward),
+ *   z_save [E,C,f] or NULL (pre-activation, needed by backward), y [E,C,h].
+ */
+moe_status_t moe_expert_ffn_fwd(const moe_shape_t *shape, const void *buf, const void *w1, const void *w2,
+                                const int32_t *kept, void *z_save, void *hact, void *y, void *ws,
+                                size_t ws_bytes, void *stream);
+
+/*
+ * Combine (Section 3, step 7, local half: tokens come back to their original position; the
+ * gate probability weights the expert's output).
+ *   out[t,:] = gate_p[t] * y[expert[t], slot[t], :]  if slot[t] >= 0, else 0.
+ *   y [E,C,h], expert [T], slot [T], gate_p [T], out [T,h].
+ */
+moe_status_t moe_combine(const moe_shape_t *shape, const void *y, const int32_t *expert, const int32_t *slot,
+                         const float *gate_p, void *out, void *stream);
+
+/* ---- backward (end of Section 3: the same steps in reverse order) ---- */
+
+/*
+ * Combine backward.
+ *   d_y[e_t,s_t,:] = gate_p[t] * d_out[t,:] ;  d_gate_p[t] = <d_out[t,:], y[e_t,s_t,:]>
+ *   for kept tokens; d_gate_p[t] = 0 for dropped tokens; empty slots of d_y are set to 0.
+ *   d_out [T,h], y [E,C,h], token_of_slot [E,C], gate_p [T], d_y [E,C,h], d_gate_p [T] f32.
+ */
+moe_status_t moe_combine_bwd(const moe_shape_t *shape, const void *d_out, const void *y,
+                             const int32_t *token_of_slot, const int32_t *slot, const float *gate_p, void *d_y,
+                             float *d_gate_p, void *stream);
+
+/*
+ * Expert FFN backward.
+ *   d_h = d_y w2[e]^T ;  d_z = d_h * GeLU'(z_save) ;  d_w2[e] = hact^T d_y ;
+ *   d_w1[e] = buf^T d_z ;  d_buf = d_z w1[e]^T          (rows r < kept[e] only)
+ * d_w1, d_w2 are overwritten (one micro-batch), in `dtype` with fp32 accumulation; an expert
+ * with kept[e] = 0 gets zero gradients.  Rows r >= kept[e] of d_buf are not written.
+ * Uses E*C*f*sizeof(dtype) bytes of workspace for d_z.
+ */
+moe_status_t moe_expert_ffn_bwd(const moe_shape_t *shape, const void *d_y, const void *buf, const void *z_save,
+                                const void *hact, const void *w1, const void *w2, const int32_t *kept,
+                                void *d_buf, void *d_w1, void *d_w2, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Dispatch backward:  d_x[t,:] = d_buf[expert[t], slot[t], :] if slot[t] >= 0 else 0.
+ *   d_buf [E,C,h], expert [T], slot [T], d_x [T,h].
+ */
+moe_status_t moe_dispatch_bwd(const moe_shape_t *shape, const void *d_buf, const int32_t *expert,
+                              const int32_t *slot, void *d_x, void *stream);
+
+/*
+ * Gate backward (the gate only receives gradient through p_t).
+ *   d_logits[t,j] = d_gate_p[t] * p_t * ([j == e_t] - probs[t,j])
+ *   d_w_gate = x^T d_logits ;  d_x_accum[t,:] += d_logits[t,:] w_gate^T   (if d_x_accum != NULL)
+ *   d_gate_p [T] f32, probs [T,E] f32, expert [T], x [T,h], w_gate [h,E] f32,
+ *   d_logits [T,E] f32 (out), d_w_gate [h,E] f32 (out, overwritten) or NULL,
+ *   d_x_accum [T,h] dtype (in/out) or NULL.
+ */
+moe_status_t moe_gate_bwd(const moe_shape_t *shape, const float *d_gate_p, const float *probs,
+                          const int32_t *expert, const void *x, const float *w_gate, float *d_logits,
+                          float *d_w_gate, void *d_x_accum, void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_TED_H */

@@ -1,0 +1,281 @@
+// Gate (routing function: linear map, softmax, top-1) and capacity-limited slot assignment.
+//
+// bf16 tokens: logits = X Wg on the matrix cores in one pass over X.  Wg stays fp32-accurate
+// by splitting every weight into three bf16 pieces (hi + mid + lo == w to ~2^-24) and issuing
+// three bf16 MFMAs into one fp32 accumulator; bf16 x bf16 products are exact in fp32, so the
+// result has fp32 dot-product accuracy while X is streamed once at HBM speed.
+// fp32 tokens: plain fp32 FMA dot products (small workloads only).
+//
+// Routing: two small kernels.  (1) per-1024-token block histograms (integer LDS atomics: the
+// result does not depend on their order); (2) every block adds the histograms of the blocks
+// before it, ranks its own tokens with wave ballots (token order inside a wave = lane order),
+// and writes slot / token_of_slot; the last block writes counts and kept.
+#include "moe_common.h"
+
+namespace moe {
+
+// ------------------------------------------------------------------ weight split
+// ws layout: 3 planes [Epad][h] bf16 (k contiguous), rows >= E are zero.
+__global__ void gate_split_wg_kernel(const float *wg, bf16_t *planes, int h, int E, int Epad) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t n = (int64_t)Epad * h;
+    if (i >= n) return;
+    int e = (int)(i / h), k = (int)(i % h);
+    float w = e < E ? wg[(int64_t)k * E + e] : 0.f;
+    bf16_t hi = f32_to_bf16(w);
+    float r1 = w - bf16_to_f32(hi);
+    bf16_t mid = f32_to_bf16(r1);
+    float r2 = r1 - bf16_to_f32(mid);
+    bf16_t lo = f32_to_bf16(r2);
+    planes[i] = hi;
+    planes[n + i] = mid;
+    planes[2 * n + i] = lo;
+}
+
+// ------------------------------------------------------------------ softmax + top-1 of one row held in LDS/global
+// row: E fp32 logits (already biased).  Returns expert and p; optionally writes probs.
+__device__ __forceinline__ void softmax_top1_row(const float *row, int rstride, int E, float *probs_out,
+                                                 int32_t *expert_out, float *p_out) {
+    float best = row[0];
+    int bi = 0;
+    for (int j = 1; j < E; ++j) {
+        float v = row[j * rstride];
+        if (v > best) { best = v; bi = j; }      // strict: the lowest index among equal maxima wins
+    }
+    float denom = 0.f;
+    for (int j = 0; j < E; ++j) denom += expf(row[j * rstride] - best);
+    float inv = 1.0f / denom;
+    *expert_out = bi;
+    *p_out = inv;
+    if (probs_out)
+        for (int j = 0; j < E; ++j) probs_out[j] = expf(row[j * rstride] - best) * inv;
+}
+
+// ------------------------------------------------------------------ fused gate, bf16 tokens
+// Workgroup: 256 threads = 4 waves, 16*R tokens.  Wave w takes k-steps w, w+4, ... (32 k each);
+// the four partial [16R x Epad] tiles are summed through LDS in a fixed order.
+template <int NT, int R>
+__global__ __launch_bounds__(256) void gate_bf16_kernel(const bf16_t *x, const bf16_t *planes, const float *bias,
+                                                         float *logits, float *probs, int32_t *expert,
+                                                         float *gate_p, int64_t T, int h, int E) {
+    constexpr int EP = NT * 16;
+    constexpr int TM = 16 * R;
+    __shared__ float part[4][TM][EP + 1];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t t0 = (int64_t)blockIdx.x * TM;
+    const int i16 = lane & 15, g = lane >> 4;
+    const int64_t plane = (int64_t)EP * h;
+
+    f32x4 acc[R][NT];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int n = 0; n < NT; ++n) acc[r][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int nsteps = (h + 31) / 32;
+    for (int s = wave; s < nsteps; s += 4) {
+        const int k = s * 32 + g * 8;
+        const bool kin = k < h;
+        bf16x8 a[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            int64_t t = t0 + r * 16 + i16;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (kin && t < T) v = __builtin_nontemporal_load((const u32x4 *)(x + t * h + k));
+            a[r] = __builtin_bit_cast(bf16x8, v);
+        }
+#pragma unroll
+        for (int n = 0; n < NT; ++n) {
+#pragma unroll
+            for (int p = 0; p < 3; ++p) {
+                u32x4 v = {0u, 0u, 0u, 0u};
+                if (kin) v = *(const u32x4 *)(planes + p * plane + (int64_t)(n * 16 + i16) * h + k);
+                bf16x8 b = __builtin_bit_cast(bf16x8, v);
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+                    acc[r][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[r], b, acc[r][n], 0, 0, 0);
+            }
+        }
+    }
+    // 16x16 result: lane holds column (expert) lane%16, rows (tokens) 4*(lane/16) + v
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int n = 0; n < NT; ++n)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) part[wave][r * 16 + g * 4 + v][n * 16 + i16] = acc[r][n][v];
+    __syncthreads();
+    for (int idx = tid; idx < TM * E; idx += 256) {
+        int tt = idx / E, j = idx - tt * E;
+        float v = ((part[0][tt][j] + part[1][tt][j]) + part[2][tt][j]) + part[3][tt][j];
+        if (bias) v += bias[j];
+        part[0][tt][j] = v;
+        if (t0 + tt < T) logits[(t0 + tt) * E + j] = v;
+    }
+    __syncthreads();
+    if (tid < TM && t0 + tid < T) {
+        int64_t t = t0 + tid;
+        softmax_top1_row(&part[0][tid][0], 1, E, probs ? probs + t * E : nullptr, expert + t, gate_p + t);
+    }
+}
+
+// ------------------------------------------------------------------ fp32 tokens: logits by fp32 FMA, one wave per token
+__global__ __launch_bounds__(256) void gate_logits_f32_kernel(const float *x, const float *wg, const float *bias,
+                                                              float *logits, int64_t T, int h, int E) {
+    const int lane = threadIdx.x & 63;
+    const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= T) return;
+    for (int j0 = 0; j0 < E; j0 += 16) {
+        float acc[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[j] = 0.f;
+        for (int k = lane; k < h; k += 64) {
+            float xv = x[t * h + k];
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (j0 + j < E) acc[j] = fmaf(xv, wg[(int64_t)k * E + j0 + j], acc[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            float v = acc[j];
+            for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+            if (lane == 0 && j0 + j < E) logits[t * E + j0 + j] = v + (bias ? bias[j0 + j] : 0.f);
+        }
+    }
+}
+
+// softmax + top-1 from stored logits, one thread per token
+__global__ void gate_softmax_top1_kernel(const float *logits, float *probs, int32_t *expert, float *gate_p,
+                                         int64_t T, int E) {
+    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    softmax_top1_row(logits + t * E, 1, E, probs ? probs + t * E : nullptr, expert + t, gate_p + t);
+}
+
+// ------------------------------------------------------------------ routing
+constexpr int RB = 1024;   // tokens per routing block
+
+__global__ __launch_bounds__(RB) void route_hist_kernel(const int32_t *expert, int32_t *hist, int32_t *token_of_slot,
+                                                         int64_t T, int E, int64_t EC) {
+    __shared__ int32_t h[256];
+    const int tid = threadIdx.x;
+    if (tid < E) h[tid] = 0;
+    __syncthreads();
+    int64_t t = (int64_t)blockIdx.x * RB + tid;
+    if (t < T) atomicAdd(&h[expert[t]], 1);
+    __syncthreads();
+    if (tid < E) hist[(int64_t)blockIdx.x * E + tid] = h[tid];
+    for (int64_t i = (int64_t)blockIdx.x * RB + tid; i < EC; i += (int64_t)gridDim.x * RB) token_of_slot[i] = -1;
+}
+
+__global__ __launch_bounds__(RB) void route_slot_kernel(const int32_t *expert, const int32_t *hist, int32_t *slot,
+                                                         int32_t *counts, int32_t *kept, int32_t *token_of_slot,
+                                                         int64_t T, int E, int64_t C) {
+    __shared__ int32_t base[256];
+    __shared__ int32_t wcnt[RB / 64][256];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = blockIdx.x;
+    for (int i = tid; i < (RB / 64) * 256; i += RB) (&wcnt[0][0])[i] = 0;
+    if (tid < E) {
+        int32_t s = 0;
+        for (int bb = 0; bb < b; ++bb) s += hist[(int64_t)bb * E + tid];
+        base[tid] = s;
+    }
+    __syncthreads();
+    const int64_t t = (int64_t)b * RB + tid;
+    const int e = t < T ? expert[t] : -1;
+    int rank = 0;
+    unsigned long long remaining = __ballot(e >= 0);
+    while (remaining) {
+        const int leader = __ffsll((long long)remaining) - 1;
+        const int e0 = __shfl(e, leader);
+        const unsigned long long m = __ballot(e == e0);
+        if (e == e0) {
+            rank = __popcll(m & ((1ull << lane) - 1ull));
+            if (lane == leader) wcnt[wave][e0] = __popcll(m);
+        }
+        remaining &= ~m;
+    }
+    __syncthreads();
+    if (tid < E) {       // exclusive prefix over the block's waves, in wave order
+        int32_t s = base[tid];
+        for (int w = 0; w < RB / 64; ++w) {
+            int32_t c = wcnt[w][tid];
+            wcnt[w][tid] = s;
+            s += c;
+        }
+        if (b == (int)gridDim.x - 1) {
+            counts[tid] = s;
+            kept[tid] = s < C ? s : (int32_t)C;
+        }
+    }
+    __syncthreads();
+    if (e >= 0) {
+        const int64_t s = (int64_t)wcnt[wave][e] + rank;
+        if (s < C) {
+            slot[t] = (int32_t)s;
+            token_of_slot[(int64_t)e * C + s] = (int32_t)t;
+        } else {
+            slot[t] = -1;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ host side
+size_t gate_ws_bytes(const moe_shape_t *sh) {
+    int NT = 1;
+    while (NT * 16 < sh->E) NT *= 2;
+    size_t planes = (size_t)3 * NT * 16 * sh->h * 2;
+    size_t hist = (size_t)((sh->T + RB - 1) / RB) * sh->E * 4;
+    return ((planes + 255) / 256) * 256 + ((hist + 255) / 256) * 256;
+}
+
+template <int NT, int R>
+static void launch_gate_bf16(const moe_shape_t *sh, const void *x, const bf16_t *planes, const float *bias,
+                             float *logits, float *probs, int32_t *expert, float *gate_p, hipStream_t s) {
+    const int TM = 16 * R;
+    dim3 grid((unsigned)((sh->T + TM - 1) / TM));
+    hipLaunchKernelGGL((gate_bf16_kernel<NT, R>), grid, dim3(256), 0, s, (const bf16_t *)x, planes, bias, logits,
+                       probs, expert, gate_p, sh->T, sh->h, sh->E);
+}
+
+moe_status_t run_gate(const moe_shape_t *sh, const void *x, const float *w_gate, const float *bias, float *logits,
+                      float *probs, int32_t *expert, float *gate_p, int32_t *slot, int32_t *counts, int32_t *kept,
+                      int32_t *token_of_slot, void *ws, hipStream_t s) {
+    int NT = 1;
+    while (NT * 16 < sh->E) NT *= 2;
+    const size_t planes_bytes = (((size_t)3 * NT * 16 * sh->h * 2 + 255) / 256) * 256;
+    bf16_t *planes = (bf16_t *)ws;
+    int32_t *hist = (int32_t *)((char *)ws + planes_bytes);
+    const int64_t T = sh->T;
+    if (x == nullptr) {
+        hipLaunchKernelGGL(gate_softmax_top1_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, s, logits,
+                           probs, expert, gate_p, T, sh->E);
+    } else if (sh->dtype == MOE_F32) {
+        hipLaunchKernelGGL(gate_logits_f32_kernel, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, s, (const float *)x,
+                           w_gate, bias, logits, T, sh->h, sh->E);
+        hipLaunchKernelGGL(gate_softmax_top1_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, s, logits,
+                           probs, expert, gate_p, T, sh->E);
+    } else {
+        const int64_t n = (int64_t)NT * 16 * sh->h;
+        hipLaunchKernelGGL(gate_split_wg_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, w_gate, planes,
+                           sh->h, sh->E, NT * 16);
+        switch (NT) {
+            case 1: launch_gate_bf16<1, 2>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
+            case 2: launch_gate_bf16<2, 2>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
+            case 4: launch_gate_bf16<4, 2>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
+            case 8: launch_gate_bf16<8, 1>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
+            default: launch_gate_bf16<16, 1>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
+        }
+    }
+    moe_status_t st = check_launch("gate");
+    if (st != MOE_OK) return st;
+    const unsigned nb = (unsigned)((T + RB - 1) / RB);
+    hipLaunchKernelGGL(route_hist_kernel, dim3(nb), dim3(RB), 0, s, expert, hist, token_of_slot, T, sh->E,
+                       (int64_t)sh->E * sh->C);
+    hipLaunchKernelGGL(route_slot_kernel, dim3(nb), dim3(RB), 0, s, expert, hist, slot, counts, kept, token_of_slot,
+                       T, sh->E, sh->C);
+    return check_launch("route");
+}
+
+}  // namespace moe

@@ -1,0 +1,331 @@
+// extern "C" entry points: host-side validation, workspace layout, launches.  See include/moe.h
+// for the contract of every call.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include "moe_common.h"
+
+namespace moe {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+moe_status_t check_launch(const char *what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_error("%s: HIP error %d (%s)", what, (int)e, hipGetErrorString(e));
+        return MOE_ERR_HIP;
+    }
+    return MOE_OK;
+}
+
+size_t gate_ws_bytes(const moe_shape_t *sh);
+size_t gate_bwd_ws_bytes(const moe_shape_t *sh);
+moe_status_t run_gate(const moe_shape_t *, const void *, const float *, const float *, float *, float *, int32_t *,
+                      float *, int32_t *, int32_t *, int32_t *, int32_t *, void *, hipStream_t);
+moe_status_t run_dispatch(const moe_shape_t *, const void *, const int32_t *, void *, hipStream_t);
+moe_status_t run_dispatch_bwd(const moe_shape_t *, const void *, const int32_t *, const int32_t *, void *,
+                              hipStream_t);
+moe_status_t run_combine(const moe_shape_t *, const void *, const int32_t *, const int32_t *, const float *, void *,
+                         hipStream_t);
+moe_status_t run_combine_bwd(const moe_shape_t *, const void *, const void *, const int32_t *, const int32_t *,
+                             const float *, void *, float *, hipStream_t);
+moe_status_t run_gate_bwd(const moe_shape_t *, const float *, const float *, const int32_t *, const void *,
+                          const float *, float *, float *, void *, void *, hipStream_t);
+
+static size_t esize(const moe_shape_t *sh) { return sh->dtype == MOE_BF16 ? 2 : 4; }
+
+static moe_status_t check_shape(const moe_shape_t *sh) {
+    if (!sh) {
+        set_error("shape is NULL");
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (sh->T <= 0 || sh->h <= 0 || sh->E <= 0 || sh->f <= 0 || sh->C <= 0) {
+        set_error("non-positive size: T=%lld h=%d E=%d f=%d C=%lld", (long long)sh->T, sh->h, sh->E, sh->f,
+                  (long long)sh->C);
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (sh->dtype != MOE_F32 && sh->dtype != MOE_BF16) {
+        set_error("unknown dtype %d", sh->dtype);
+        return MOE_ERR_UNSUPPORTED;
+    }
+    if (sh->act != MOE_GELU_ERF && sh->act != MOE_GELU_TANH) {
+        set_error("unknown activation %d", sh->act);
+        return MOE_ERR_UNSUPPORTED;
+    }
+    if (sh->E > 256) {
+        set_error("E=%d exceeds the supported maximum of 256", sh->E);
+        return MOE_ERR_UNSUPPORTED;
+    }
+    const int mult = sh->dtype == MOE_BF16 ? 8 : 4;
+    if (sh->h % mult || sh->f % mult) {
+        set_error("h=%d and f=%d must be multiples of %d for this dtype", sh->h, sh->f, mult);
+        return MOE_ERR_UNSUPPORTED;
+    }
+    const int64_t w = sh->h > sh->f ? sh->h : sh->f;
+    if (sh->T > (int64_t)0x7fffffff || sh->C > (int64_t)0x7fffffff ||
+        (double)sh->E * (double)sh->C * (double)w >= 1099511627776.0 ||
+        (double)sh->C * (double)w * (double)esize(sh) >= 2147483648.0 ||
+        (double)sh->h * (double)sh->f * (double)esize(sh) >= 2147483648.0) {
+        set_error("shape too large: T=%lld C=%lld E=%d h=%d f=%d", (long long)sh->T, (long long)sh->C, sh->E, sh->h,
+                  sh->f);
+        return MOE_ERR_UNSUPPORTED;
+    }
+    return MOE_OK;
+}
+
+static bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
+
+#define REQUIRE_PTR(p)                                                  \
+    do {                                                                \
+        if ((p) == nullptr) {                                           \
+            set_error("%s: argument '%s' is NULL", __func__, #p);       \
+            return MOE_ERR_INVALID_ARG;                                 \
+        }                                                               \
+        if (misaligned(p)) {                                            \
+            set_error("%s: argument '%s' is not 16-byte aligned", __func__, #p); \
+            return MOE_ERR_INVALID_ARG;                                 \
+        }                                                               \
+    } while (0)
+#define OPTIONAL_PTR(p)                                                 \
+    do {                                                                \
+        if ((p) != nullptr && misaligned(p)) {                          \
+            set_error("%s: argument '%s' is not 16-byte aligned", __func__, #p); \
+            return MOE_ERR_INVALID_ARG;                                 \
+        }                                                               \
+    } while (0)
+
+static size_t round256(size_t v) { return (v + 255) / 256 * 256; }
+static size_t dz_bytes(const moe_shape_t *sh) { return round256((size_t)sh->E * sh->C * sh->f * esize(sh)); }
+
+static size_t ws_bytes_checked(const moe_shape_t *sh, int for_backward) {
+    size_t fwd = gate_ws_bytes(sh);
+    if (!for_backward) return fwd;
+    size_t bwd = dz_bytes(sh) + round256(gate_bwd_ws_bytes(sh));
+    return fwd > bwd ? fwd : bwd;
+}
+
+static moe_status_t check_ws(const char *fn, const void *ws, size_t have, size_t need) {
+    if (need == 0) return MOE_OK;
+    if (ws == nullptr || misaligned(ws)) {
+        set_error("%s: workspace is NULL or misaligned", fn);
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (have < need) {
+        set_error("%s: workspace too small: %zu bytes given, %zu needed", fn, have, need);
+        return MOE_ERR_WORKSPACE_TOO_SMALL;
+    }
+    return MOE_OK;
+}
+
+}  // namespace moe
+
+using namespace moe;
+
+extern "C" {
+
+int moe_version(void) { return 1; }
+
+int64_t moe_capacity(int64_t T, int32_t E, double capacity_factor) {
+    if (T <= 0 || E <= 0 || !(capacity_factor > 0.0)) return 0;
+    return (int64_t)std::ceil(capacity_factor * (double)T / (double)E);
+}
+
+size_t moe_workspace_bytes(const moe_shape_t *shape, int for_backward) {
+    if (check_shape(shape) != MOE_OK) return 0;
+    return ws_bytes_checked(shape, for_backward);
+}
+
+const char *moe_status_string(moe_status_t s) {
+    switch (s) {
+        case MOE_OK: return "MOE_OK";
+        case MOE_ERR_INVALID_ARG: return "MOE_ERR_INVALID_ARG";
+        case MOE_ERR_UNSUPPORTED: return "MOE_ERR_UNSUPPORTED";
+        case MOE_ERR_WORKSPACE_TOO_SMALL: return "MOE_ERR_WORKSPACE_TOO_SMALL";
+        case MOE_ERR_HIP: return "MOE_ERR_HIP";
+    }
+    return "MOE_ERR_UNKNOWN";
+}
+
+const char *moe_last_error(void) { return g_err; }
+
+moe_status_t moe_gate(const moe_shape_t *shape, const void *x, const float *w_gate, const float *logit_bias,
+                      float *logits, float *probs, int32_t *expert, float *gate_p, int32_t *slot, int32_t *counts,
+                      int32_t *kept, int32_t *token_of_slot, void *ws, size_t ws_bytes, void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if (x != nullptr) {
+        REQUIRE_PTR(x);
+        REQUIRE_PTR(w_gate);
+        OPTIONAL_PTR(logit_bias);
+    }
+    REQUIRE_PTR(logits);
+    OPTIONAL_PTR(probs);
+    REQUIRE_PTR(expert);
+    REQUIRE_PTR(gate_p);
+    REQUIRE_PTR(slot);
+    REQUIRE_PTR(counts);
+    REQUIRE_PTR(kept);
+    REQUIRE_PTR(token_of_slot);
+    st = check_ws("moe_gate", ws, ws_bytes, gate_ws_bytes(shape));
+    if (st != MOE_OK) return st;
+    return run_gate(shape, x, w_gate, logit_bias, logits, probs, expert, gate_p, slot, counts, kept, token_of_slot, ws,
+                    (hipStream_t)stream);
+}
+
+moe_status_t moe_dispatch(const moe_shape_t *shape, const void *x, const int32_t *token_of_slot, void *buf,
+                          void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    REQUIRE_PTR(x);
+    REQUIRE_PTR(token_of_slot);
+    REQUIRE_PTR(buf);
+    return run_dispatch(shape, x, token_of_slot, buf, (hipStream_t)stream);
+}
+
+moe_status_t moe_expert_ffn_fwd(const moe_shape_t *shape, const void *buf, const void *w1, const void *w2,
+                                const int32_t *kept, void *z_save, void *hact, void *y, void *ws, size_t ws_bytes,
+                                void *stream) {
+    (void)ws;
+    (void)ws_bytes;
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    REQUIRE_PTR(buf);
+    REQUIRE_PTR(w1);
+    REQUIRE_PTR(w2);
+    REQUIRE_PTR(kept);
+    OPTIONAL_PTR(z_save);
+    REQUIRE_PTR(hact);
+    REQUIRE_PTR(y);
+    const moe_shape_t &s = *shape;
+    const bool bf = s.dtype == MOE_BF16;
+    GemmDesc g1 = {};
+    g1.A = buf; g1.B = w1; g1.C = hact; g1.C2 = z_save; g1.kept = kept;
+    g1.strideA = s.C * s.h; g1.strideB = (int64_t)s.h * s.f; g1.strideC = s.C * s.f;
+    g1.M = (int32_t)s.C; g1.N = s.f; g1.K = s.h; g1.lda = s.h; g1.ldb = s.f; g1.ldc = s.f; g1.E = s.E;
+    g1.a_xc = 0; g1.b_xc = 1; g1.rows_from_kept = 1; g1.epi = EPI_GELU; g1.act = s.act;
+    st = bf ? launch_gemm_bf16(g1, (hipStream_t)stream) : launch_gemm_f32(g1, (hipStream_t)stream);
+    if (st != MOE_OK) return st;
+    GemmDesc g2 = {};
+    g2.A = hact; g2.B = w2; g2.C = y; g2.kept = kept;
+    g2.strideA = s.C * s.f; g2.strideB = (int64_t)s.f * s.h; g2.strideC = s.C * s.h;
+    g2.M = (int32_t)s.C; g2.N = s.h; g2.K = s.f; g2.lda = s.f; g2.ldb = s.h; g2.ldc = s.h; g2.E = s.E;
+    g2.a_xc = 0; g2.b_xc = 1; g2.rows_from_kept = 1; g2.epi = EPI_STORE; g2.act = s.act;
+    return bf ? launch_gemm_bf16(g2, (hipStream_t)stream) : launch_gemm_f32(g2, (hipStream_t)stream);
+}
+
+moe_status_t moe_combine(const moe_shape_t *shape, const void *y, const int32_t *expert, const int32_t *slot,
+                         const float *gate_p, void *out, void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    REQUIRE_PTR(y);
+    REQUIRE_PTR(expert);
+    REQUIRE_PTR(slot);
+    REQUIRE_PTR(gate_p);
+    REQUIRE_PTR(out);
+    return run_combine(shape, y, expert, slot, gate_p, out, (hipStream_t)stream);
+}
+
+moe_status_t moe_combine_bwd(const moe_shape_t *shape, const void *d_out, const void *y, const int32_t *token_of_slot,
+                             const int32_t *slot, const float *gate_p, void *d_y, float *d_gate_p, void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    REQUIRE_PTR(d_out);
+    REQUIRE_PTR(y);
+    REQUIRE_PTR(token_of_slot);
+    REQUIRE_PTR(slot);
+    REQUIRE_PTR(gate_p);
+    REQUIRE_PTR(d_y);
+    REQUIRE_PTR(d_gate_p);
+    return run_combine_bwd(shape, d_out, y, token_of_slot, slot, gate_p, d_y, d_gate_p, (hipStream_t)stream);
+}
+
+moe_status_t moe_expert_ffn_bwd(const moe_shape_t *shape, const void *d_y, const void *buf, const void *z_save,
+                                const void *hact, const void *w1, const void *w2, const int32_t *kept, void *d_buf,
+                                void *d_w1, void *d_w2, void *ws, size_t ws_bytes, void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    REQUIRE_PTR(d_y);
+    REQUIRE_PTR(buf);
+    REQUIRE_PTR(z_save);
+    REQUIRE_PTR(hact);
+    REQUIRE_PTR(w1);
+    REQUIRE_PTR(w2);
+    REQUIRE_PTR(kept);
+    REQUIRE_PTR(d_buf);
+    REQUIRE_PTR(d_w1);
+    REQUIRE_PTR(d_w2);
+    st = check_ws("moe_expert_ffn_bwd", ws, ws_bytes, dz_bytes(shape));
+    if (st != MOE_OK) return st;
+    const moe_shape_t &s = *shape;
+    const bool bf = s.dtype == MOE_BF16;
+    hipStream_t hs = (hipStream_t)stream;
+    void *d_z = ws;
+    auto run = [&](const GemmDesc &g) { return bf ? launch_gemm_bf16(g, hs) : launch_gemm_f32(g, hs); };
+    // d_z = (d_y w2^T) * act'(z)          A = d_y [M,h], B = w2 [f,h] = [N,K]
+    GemmDesc g = {};
+    g.A = d_y; g.B = w2; g.C = d_z; g.Zin = z_save; g.kept = kept;
+    g.strideA = s.C * s.h; g.strideB = (int64_t)s.f * s.h; g.strideC = s.C * s.f;
+    g.M = (int32_t)s.C; g.N = s.f; g.K = s.h; g.lda = s.h; g.ldb = s.h; g.ldc = s.f; g.E = s.E;
+    g.a_xc = 0; g.b_xc = 0; g.rows_from_kept = 1; g.epi = EPI_DGELU; g.act = s.act;
+    if ((st = run(g)) != MOE_OK) return st;
+    // d_w2 = hact^T d_y                   A = hact [K=rows, M=f], B = d_y [K=rows, N=h]
+    g = GemmDesc{};
+    g.A = hact; g.B = d_y; g.C = d_w2; g.kept = kept;
+    g.strideA = s.C * s.f; g.strideB = s.C * s.h; g.strideC = (int64_t)s.f * s.h;
+    g.M = s.f; g.N = s.h; g.K = (int32_t)s.C; g.lda = s.f; g.ldb = s.h; g.ldc = s.h; g.E = s.E;
+    g.a_xc = 1; g.b_xc = 1; g.rows_from_kept = 0; g.epi = EPI_STORE; g.act = s.act;
+    if ((st = run(g)) != MOE_OK) return st;
+    // d_w1 = buf^T d_z                    A = buf [K=rows, M=h], B = d_z [K=rows, N=f]
+    g = GemmDesc{};
+    g.A = buf; g.B = d_z; g.C = d_w1; g.kept = kept;
+    g.strideA = s.C * s.h; g.strideB = s.C * s.f; g.strideC = (int64_t)s.h * s.f;
+    g.M = s.h; g.N = s.f; g.K = (int32_t)s.C; g.lda = s.h; g.ldb = s.f; g.ldc = s.f; g.E = s.E;
+    g.a_xc = 1; g.b_xc = 1; g.rows_from_kept = 0; g.epi = EPI_STORE; g.act = s.act;
+    if ((st = run(g)) != MOE_OK) return st;
+    // d_buf = d_z w1^T                    A = d_z [M,f], B = w1 [h,f] = [N,K]
+    g = GemmDesc{};
+    g.A = d_z; g.B = w1; g.C = d_buf; g.kept = kept;
+    g.strideA = s.C * s.f; g.strideB = (int64_t)s.h * s.f; g.strideC = s.C * s.h;
+    g.M = (int32_t)s.C; g.N = s.h; g.K = s.f; g.lda = s.f; g.ldb = s.f; g.ldc = s.h; g.E = s.E;
+    g.a_xc = 0; g.b_xc = 0; g.rows_from_kept = 1; g.epi = EPI_STORE; g.act = s.act;
+    return run(g);
+}
+
+moe_status_t moe_dispatch_bwd(const moe_shape_t *shape, const void *d_buf, const int32_t *expert, const int32_t *slot,
+                              void *d_x, void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    REQUIRE_PTR(d_buf);
+    REQUIRE_PTR(expert);
+    REQUIRE_PTR(slot);
+    REQUIRE_PTR(d_x);
+    return run_dispatch_bwd(shape, d_buf, expert, slot, d_x, (hipStream_t)stream);
+}
+
+moe_status_t moe_gate_bwd(const moe_shape_t *shape, const float *d_gate_p, const float *probs, const int32_t *expert,
+                          const void *x, const float *w_gate, float *d_logits, float *d_w_gate, void *d_x_accum,
+                          void *ws, size_t ws_bytes, void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    REQUIRE_PTR(d_gate_p);
+    REQUIRE_PTR(probs);
+    REQUIRE_PTR(expert);
+    REQUIRE_PTR(x);
+    REQUIRE_PTR(w_gate);
+    REQUIRE_PTR(d_logits);
+    OPTIONAL_PTR(d_w_gate);
+    OPTIONAL_PTR(d_x_accum);
+    st = check_ws("moe_gate_bwd", ws, ws_bytes, d_w_gate ? gate_bwd_ws_bytes(shape) : 0);
+    if (st != MOE_OK) return st;
+    return run_gate_bwd(shape, d_gate_p, probs, expert, x, w_gate, d_logits, d_w_gate, d_x_accum, ws,
+                        (hipStream_t)stream);
+}
+
+}  // extern "C"

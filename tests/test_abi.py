@@ -1,0 +1,86 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and rejects bad arguments before launching anything."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2303_06318_amd import moe
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "moe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = moe.lib()
+    names = declared_functions()
+    assert len(names) >= 13
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(moe.EXPORTS) == names
+    # the binding offers the same names
+    for n in names:
+        if n not in ("moe_status_string", "moe_last_error"):
+            assert hasattr(moe, n), n
+
+
+def test_capacity_and_workspace_are_pure_host_functions():
+    assert moe.moe_capacity(16384, 16, 1.25) == 1280
+    assert moe.moe_capacity(256, 4, 1.0) == 64
+    assert moe.moe_capacity(10, 3, 1.0) == 4
+    assert moe.moe_capacity(0, 3, 1.0) == 0 and moe.moe_capacity(10, 0, 1.0) == 0
+    sh = moe.make_shape(16384, 4096, 16, 4096, 1280)
+    fw, bw = moe.moe_workspace_bytes(sh, False), moe.moe_workspace_bytes(sh, True)
+    assert 0 < fw < bw
+    assert bw >= 16 * 1280 * 4096 * 2
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(T=0), moe.MOE_ERR_INVALID_ARG),
+    (dict(E=0), moe.MOE_ERR_INVALID_ARG),
+    (dict(Cap=-1), moe.MOE_ERR_INVALID_ARG),
+    (dict(h=4100), moe.MOE_ERR_UNSUPPORTED),      # not a multiple of 8 for bf16
+    (dict(E=257), moe.MOE_ERR_UNSUPPORTED),
+    (dict(dtype=7), moe.MOE_ERR_UNSUPPORTED),
+    (dict(act=9), moe.MOE_ERR_UNSUPPORTED),
+])
+def test_bad_shapes_are_rejected_without_launch(kw, status):
+    base = dict(T=1024, h=512, E=8, f=512, Cap=128, dtype=moe.MOE_BF16, act=moe.MOE_GELU_ERF)
+    base.update(kw)
+    sh = moe.make_shape(**base)
+    assert moe.moe_workspace_bytes(sh, False) == 0
+    fake = 4096   # never dereferenced: validation fails first
+    with pytest.raises(moe.MoeError) as ei:
+        moe.moe_dispatch(sh, fake, fake, fake, stream=0)
+    assert ei.value.status == status
+
+
+def test_null_misaligned_and_workspace_errors():
+    sh = moe.make_shape(1024, 512, 8, 512, 128)
+    a = 4096
+    with pytest.raises(moe.MoeError) as ei:
+        moe.moe_combine(sh, a, a, None, a, a, stream=0)
+    assert ei.value.status == moe.MOE_ERR_INVALID_ARG and "slot" in str(ei.value)
+    with pytest.raises(moe.MoeError) as ei:
+        moe.moe_combine(sh, a, a, a + 4, a, a, stream=0)
+    assert ei.value.status == moe.MOE_ERR_INVALID_ARG and "aligned" in str(ei.value)
+    # workspace too small: pass a raw pointer with a byte count through the C function directly
+    L = moe.lib()
+    p = C.c_void_p(a)
+    st = L.moe_gate(C.byref(sh), p, p, None, p, None, p, p, p, p, p, p, p, 16, None)
+    assert st == moe.MOE_ERR_WORKSPACE_TOO_SMALL
+    assert b"workspace" in L.moe_last_error()
+    assert moe.status_string(st) == "MOE_ERR_WORKSPACE_TOO_SMALL"
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(moe, "_lib", None)
+    monkeypatch.setattr(moe, "LIB_PATH", "/nonexistent/libmoe_ted.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        moe.lib()
