@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE-layer hot path on one MI355X.
+
+A step is one pass of the whole layer over one batch of seeded synthetic tokens that are already
+resident in HBM: gate + routing, dispatch, expert FFN, combine, and (for the fwd+bwd workload)
+combine backward, expert FFN backward, dispatch backward and gate backward.  The default
+workload is the 6.7B-base, 16-expert, tensor-parallel-shard layer forward + backward
+(T=16384, h=4096, E=16, f=4096, capacity factor 1.25).
+
+Prints ONE JSON line: tokens/s of the whole step, the roofline figure of the dominant kernel (the
+grouped bf16 MFMA GEMM, timed live with events on the launch stream) and the CPU oracle timed on
+a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/);
+# keyed by workload name.  None until measured.
+MEASURED_GEMM_TRAFFIC_BYTES = {}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg5_6p7b_tp4_fwdbwd")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=768)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU's share of the layer on ONE GPU; --gpus must be 1 "
+              "(nothing in this build crosses GPUs)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2303_06318_amd import moe, synth
+    from paper_2303_06318_amd.layer import MoeLayer
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 3
+    moe.lib()     # fail loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+    wl = synth.WORKLOADS[args.workload]
+    assert wl.dtype == "bf16", "the benchmark workloads are the bf16 ones"
+    inp = synth.make_inputs(wl)
+
+    def up(name):
+        a = inp.bits.get(name)
+        return None if a is None else torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+
+    x, w1, w2, d_out = up("x"), up("w1"), up("w2"), up("d_out")
+    wg = torch.from_numpy(inp.wg).cuda()
+    bias = None if inp.logit_bias is None else torch.from_numpy(inp.logit_bias).cuda()
+    layer = MoeLayer(wl.T, wl.h, wl.E, wl.f, wl.C, moe.MOE_BF16, moe.MOE_GELU_ERF, backward=wl.backward)
+    sh = layer.shape
+
+    phases = ["gate", "dispatch", "ffn_fwd", "combine"] + (
+        ["combine_bwd", "ffn_bwd", "dispatch_bwd", "gate_bwd"] if wl.backward else [])
+
+    def step(ev=None):
+        def mark(i):
+            if ev is not None:
+                ev[i].record()
+        mark(0)
+        moe.moe_gate(sh, x, wg, bias, layer.logits, layer.probs, layer.expert, layer.gate_p, layer.slot, layer.counts,
+                     layer.kept, layer.token_of_slot, layer.ws)
+        mark(1)
+        moe.moe_dispatch(sh, x, layer.token_of_slot, layer.buf)
+        mark(2)
+        moe.moe_expert_ffn_fwd(sh, layer.buf, w1, w2, layer.kept, layer.z_save, layer.hact, layer.y, layer.ws)
+        mark(3)
+        moe.moe_combine(sh, layer.y, layer.expert, layer.slot, layer.gate_p, layer.out)
+        mark(4)
+        if wl.backward:
+            moe.moe_combine_bwd(sh, d_out, layer.y, layer.token_of_slot, layer.slot, layer.gate_p, layer.d_y,
+                                layer.d_gate_p)
+            mark(5)
+            moe.moe_expert_ffn_bwd(sh, layer.d_y, layer.buf, layer.z_save, layer.hact, w1, w2, layer.kept,
+                                   layer.d_buf, layer.d_w1, layer.d_w2, layer.ws)
+            mark(6)
+            moe.moe_dispatch_bwd(sh, layer.d_buf, layer.expert, layer.slot, layer.d_x)
+            mark(7)
+            moe.moe_gate_bwd(sh, layer.d_gate_p, layer.probs, layer.expert, x, wg, layer.d_logits, layer.d_w_gate,
+                             layer.d_x, layer.ws)
+            mark(8)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    nev = len(phases) + 1
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(nev)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    phase_ms = {p: 0.0 for p in phases}
+    for k in range(args.steps):
+        for i, p in enumerate(phases):
+            phase_ms[p] += events[k][i].elapsed_time(events[k][i + 1])
+    phase_ms = {p: v / args.steps for p, v in phase_ms.items()}
+
+    kept = layer.kept.cpu().numpy().astype(np.int64)
+    counts = layer.counts.cpu().numpy().astype(np.int64)
+    n_kept = int(kept.sum())
+    # dominant kernel: the grouped bf16 MFMA GEMM.  Algorithmic flops per launch = 2*h*f*N_kept
+    # (kept rows only); 2 launches in ffn_fwd, 4 in ffn_bwd.
+    n_launch = 2 + (4 if wl.backward else 0)
+    gemm_ms = phase_ms["ffn_fwd"] + (phase_ms["ffn_bwd"] if wl.backward else 0.0)
+    flops_per_launch = 2.0 * wl.h * wl.f * n_kept
+    avg_launch_ms = gemm_ms / n_launch
+    achieved = flops_per_launch / (avg_launch_ms * 1e-3) / 1e12
+    traffic = MEASURED_GEMM_TRAFFIC_BYTES.get(wl.name)
+    roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                "kernel": "gemm_bf16_kernel", "launches_per_step": n_launch,
+                "avg_launch_ms": round(avg_launch_ms, 4), "flops_per_launch": flops_per_launch}
+
+    esz = 2
+    hbm = {
+        "gate": (wl.T * wl.h * esz + wl.h * wl.E * 4 + wl.T * wl.E * 4 * (2 if wl.backward else 1) + wl.T * 8),
+        "dispatch": 2 * n_kept * wl.h * esz + wl.T * 8,
+        "combine": n_kept * wl.h * esz + wl.T * wl.h * esz + wl.T * 12,
+    }
+    if wl.backward:
+        hbm["combine_bwd"] = 3 * n_kept * wl.h * esz
+        hbm["dispatch_bwd"] = n_kept * wl.h * esz + wl.T * wl.h * esz
+        hbm["gate_bwd"] = wl.T * wl.h * esz * 3 + wl.T * wl.E * 4 * 2
+    hbm_frac = {p: round(b / (phase_ms[p] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) for p, b in hbm.items()}
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        from oracle import moe_oracle as orc
+        S = min(args.cpu_sample_tokens, wl.T)
+        Cs = orc.capacity(S, wl.E, wl.capacity_factor)
+        tc0 = time.perf_counter()
+        fw = orc.layer_forward(inp.x[:S], inp.wg, inp.w1, inp.w2, Cs, logit_bias=inp.logit_bias)
+        if wl.backward:
+            orc.layer_backward(fw, inp.d_out[:S], inp.x[:S], inp.wg, inp.w1, inp.w2)
+        tc1 = time.perf_counter()
+        cpu_baseline = {"value": round(S / (tc1 - tc0), 2), "unit": "tokens/s", "cores": orc.max_threads(),
+                        "kind": "oracle",
+                        "sample": f"first {S} tokens of the same workload through the whole layer "
+                                  f"({'fwd+bwd' if wl.backward else 'fwd'}, all {wl.E} experts, capacity {Cs}), "
+                                  f"{tc1 - tc0:.1f} s"}
+
+    out = {
+        "metric": "MoE-layer tokens/sec " + ("fwd+bwd" if wl.backward else "fwd") + f" at h={wl.h},E={wl.E} (1 GPU)",
+        "value": round(wl.T / (ms_per_step * 1e-3), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "T": wl.T, "h": wl.h, "E": wl.E, "f": wl.f, "C": wl.C,
+                   "capacity_factor": wl.capacity_factor, "n_kept": n_kept,
+                   "count_min": int(counts.min()), "count_max": int(counts.max()), "seed": wl.seed,
+                   "pass": "fwd+bwd" if wl.backward else "fwd"},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "phase_ms": {p: round(v, 4) for p, v in phase_ms.items()},
+        "hbm_frac_of_8TBs": hbm_frac,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
