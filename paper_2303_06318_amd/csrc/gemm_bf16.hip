@@ -24,30 +24,86 @@ constexpr int STAGE_ELEMS = 256 * KC_LD;   // == 64 * XC_LD
 static_assert(256 * KC_LD == 64 * XC_LD, "both tile shapes share one stage size");
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
+// GeLU for the bf16 epilogues: erf by the Abramowitz-Stegun 7.1.26 rational form (absolute error
+// 1.5e-7, far below bf16 resolution) with hardware exp and reciprocal; no branches.
+__device__ __forceinline__ float erf_exp_fast(float u, float &ex) {   // u >= 0; ex = exp(-u*u)
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, u, 1.0f));
+    ex = __expf(-u * u);
+    float p = fmaf(t, 1.061405429f, -1.453152027f);
+    p = fmaf(t, p, 1.421413741f);
+    p = fmaf(t, p, -0.284496736f);
+    p = fmaf(t, p, 0.254829592f);
+    return 1.0f - p * t * ex;
+}
+__device__ __forceinline__ float tanh_fast(float u) {
+    const float e2 = __expf(2.0f * u);
+    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(e2 + 1.0f);
+}
+__device__ __forceinline__ float gelu_fast(float x, int act) {
+    if (act == MOE_GELU_TANH) {
+        const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+        return 0.5f * x * (1.0f + tanh_fast(u));
+    }
+    float ex;
+    const float er = erf_exp_fast(fabsf(x) * 0.7071067811865476f, ex);
+    return 0.5f * x * (1.0f + copysignf(er, x));
+}
+__device__ __forceinline__ float gelu_grad_fast(float x, int act) {
+    if (act == MOE_GELU_TANH) {
+        const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+        const float th = tanh_fast(u);
+        const float du = 0.7978845608028654f * (1.0f + 0.134145f * x * x);
+        return 0.5f * (1.0f + th) + 0.5f * x * (1.0f - th * th) * du;
+    }
+    float ex;
+    const float er = erf_exp_fast(fabsf(x) * 0.7071067811865476f, ex);
+    return 0.5f * (1.0f + copysignf(er, x)) + x * ex * 0.3989422804014327f;
+}
+
 struct TileLoader {
     u32x4 r[4];
 };
 
+// Buffer resource over one expert's operand: loads beyond `bytes` (and lanes whose offset is forced
+// out of range) return zero without a branch.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+constexpr uint32_t OOB = 0x80000000u;
+
 // global -> registers for one operand's k-tile.  xc: tile is [64 k][256 x]; else [256 x][64 k].
+// xoff[p] is the byte offset of this thread's p-th 16-byte piece at k = 0 (already out of range
+// when its row/column lies outside the operand); the k part is added per tile.
 template <bool XC>
-__device__ __forceinline__ void load_tile(TileLoader &t, const bf16_t *base, int ld, int x0, int xlim, int k0,
-                                          int klim, int tid) {
+__device__ __forceinline__ void loader_init(uint32_t (&xoff)[4], int ld, int x0, int xlim, int tid) {
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-        int gx, gk;
         if (XC) {
-            gx = x0 + (tid & 31) * 8;
-            gk = k0 + (tid >> 5) + 16 * p;
+            const int gx = x0 + (tid & 31) * 8;
+            const uint32_t o = ((uint32_t)((tid >> 5) + 16 * p) * ld + gx) * 2u;
+            xoff[p] = gx < xlim ? o : OOB;
         } else {
-            gx = x0 + (tid >> 3) + 64 * p;
-            gk = k0 + (tid & 7) * 8;
+            const int gx = x0 + (tid >> 3) + 64 * p;
+            const uint32_t o = ((uint32_t)gx * ld + (tid & 7) * 8) * 2u;
+            xoff[p] = gx < xlim ? o : OOB;
         }
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (gx < xlim && gk < klim) {
-            const bf16_t *ptr = XC ? base + (int64_t)gk * ld + gx : base + (int64_t)gx * ld + gk;
-            v = *(const u32x4 *)ptr;
+    }
+}
+
+template <bool XC>
+__device__ __forceinline__ void load_tile(TileLoader &t, __amdgpu_buffer_rsrc_t rsrc, const uint32_t (&xoff)[4],
+                                          int ld, int k0, int klim, int tid) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        uint32_t off;
+        if (XC) {
+            const int gk = k0 + (tid >> 5) + 16 * p;
+            off = gk < klim ? xoff[p] + (uint32_t)k0 * ld * 2u : OOB;
+        } else {
+            const int gk = k0 + (tid & 7) * 8;
+            off = gk < klim ? xoff[p] + (uint32_t)k0 * 2u : OOB;
         }
-        t.r[p] = v;
+        t.r[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0);
     }
 }
 
@@ -99,8 +155,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
     const int m0 = mti * BM, n0 = nti * BN;
     if (m0 >= Me) return;
 
-    const bf16_t *A = (const bf16_t *)d.A + (int64_t)e * d.strideA;
-    const bf16_t *B = (const bf16_t *)d.B + (int64_t)e * d.strideB;
+    const bf16_t *Ap = (const bf16_t *)d.A + (int64_t)e * d.strideA;
+    const bf16_t *Bp = (const bf16_t *)d.B + (int64_t)e * d.strideB;
+    // extent of this expert's operands in bytes (rows x row length)
+    const uint32_t a_bytes = (uint32_t)(AXC ? Ke : Me) * (uint32_t)d.lda * 2u;
+    const uint32_t b_bytes = (uint32_t)(BXC ? Ke : d.N) * (uint32_t)d.ldb * 2u;
+    const __amdgpu_buffer_rsrc_t A = make_rsrc(Ap, a_bytes), B = make_rsrc(Bp, b_bytes);
 
     __shared__ __attribute__((aligned(16))) bf16_t lds[2][2][STAGE_ELEMS];
 
@@ -116,68 +176,136 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     const int nk = (Ke + BK - 1) / BK;
+    // Software pipeline.  Per k-tile and wave: 4 k-steps of 8 MFMAs.  Fragments are double
+    // buffered (F0/F1) so every LDS read is issued one k-step (8 MFMAs) before its use; the next
+    // tile's global data sits in registers (ta/tb) for a whole tile before it is written to the
+    // other LDS stage.  Loads past K return zero (buffer bounds), so the loop body has no branches.
+    bf16x8 a0[4], b0[2], a1[4], b1[2];
     TileLoader ta, tb;
+    uint32_t xa[4], xb[4];
+    loader_init<AXC>(xa, d.lda, m0, Me, tid);
+    loader_init<BXC>(xb, d.ldb, n0, d.N, tid);
+    auto rd = [&](bf16x8(&af)[4], bf16x8(&bf)[2], int stage, int ks) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) af[i] = read_frag<AXC>(lds[stage][0], wm + i * 32, ks, lane);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) bf[j] = read_frag<BXC>(lds[stage][1], wn + j * 32, ks, lane);
+    };
+    auto mma = [&](const bf16x8(&af)[4], const bf16x8(&bf)[2]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], af[i], acc[i][j], 0, 0, 0);
+    };
     if (nk > 0) {
-        load_tile<AXC>(ta, A, d.lda, m0, Me, 0, Ke, tid);
-        load_tile<BXC>(tb, B, d.ldb, n0, d.N, 0, Ke, tid);
+        load_tile<AXC>(ta, A, xa, d.lda, 0, Ke, tid);
+        load_tile<BXC>(tb, B, xb, d.ldb, 0, Ke, tid);
         store_tile<AXC>(ta, lds[0][0], tid);
         store_tile<BXC>(tb, lds[0][1], tid);
+        load_tile<AXC>(ta, A, xa, d.lda, BK, Ke, tid);
+        load_tile<BXC>(tb, B, xb, d.ldb, BK, Ke, tid);
+        __syncthreads();
+        rd(a0, b0, 0, 0);
     }
-    __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
-        if (kt + 1 < nk) {
-            load_tile<AXC>(ta, A, d.lda, m0, Me, (kt + 1) * BK, Ke, tid);
-            load_tile<BXC>(tb, B, d.ldb, n0, d.N, (kt + 1) * BK, Ke, tid);
+        rd(a1, b1, cur, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        rd(a0, b0, cur, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        rd(a1, b1, cur, 3);
+        store_tile<AXC>(ta, lds[cur ^ 1][0], tid);
+        store_tile<BXC>(tb, lds[cur ^ 1][1], tid);
+        load_tile<AXC>(ta, A, xa, d.lda, (kt + 2) * BK, Ke, tid);
+        load_tile<BXC>(tb, B, xb, d.ldb, (kt + 2) * BK, Ke, tid);
+        mma(a0, b0);
+        // interleave: one MFMA, one LDS write of the staged tile, one global load of the tile after it
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
-        const bf16_t *sa = lds[cur][0], *sb = lds[cur][1];
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 af[4], bfr[2];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) af[i] = read_frag<AXC>(sa, wm + i * 32, ks, lane);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) bfr[j] = read_frag<BXC>(sb, wn + j * 32, ks, lane);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-        }
-        if (kt + 1 < nk) {
-            store_tile<AXC>(ta, lds[cur ^ 1][0], tid);
-            store_tile<BXC>(tb, lds[cur ^ 1][1], tid);
-        }
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
+        rd(a0, b0, cur ^ 1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
     }
 
-    // Epilogue.  Lane holds column n = lane%32 of each 32x32 block; element v is row
-    // (v/4)*8 + (lane/32)*4 + v%4.
+    // Epilogue.  The MFMAs were issued with the operands swapped (B fragment first), so the
+    // accumulators hold the transposed block: lane owns output row m = lane%32 and, per group of
+    // four registers, four consecutive columns n = (v/4)*8 + (lane/32)*4 + v%4.  The tile is
+    // converted to bf16, staged in LDS (the operand stages are free now; reads still in flight
+    // from the loop's last prefetch are never used) and written out as full 512-byte rows.
     bf16_t *C = (bf16_t *)d.C + (int64_t)e * d.strideC;
-    bf16_t *C2 = (EPI == EPI_GELU && d.C2) ? (bf16_t *)d.C2 + (int64_t)e * d.strideC : nullptr;
-    const bf16_t *Zin = (EPI == EPI_DGELU) ? (const bf16_t *)d.Zin + (int64_t)e * d.strideC : nullptr;
+    bf16_t *st = &lds[0][0][0];
+    constexpr int CLD = BN + 8;
+    static_assert(BM * CLD <= 4 * STAGE_ELEMS, "staging tile fits in the operand stages");
+    const int act = d.act;
+    auto for_each_quad = [&](auto fn) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int gn = n0 + wn + j * 32 + (lane & 31);
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int gm = m0 + wm + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-                if (gm < Me && gn < d.N) {
-                    const int64_t o = (int64_t)gm * d.ldc + gn;
-                    float x = acc[i][j][v];
-                    if (EPI == EPI_GELU) {
-                        if (C2) C2[o] = f32_to_bf16(x);
-                        C[o] = f32_to_bf16(act_fwd(x, d.act));
-                    } else if (EPI == EPI_DGELU) {
-                        C[o] = f32_to_bf16(x * act_grad(bf16_to_f32(Zin[o]), d.act));
-                    } else {
-                        C[o] = f32_to_bf16(x);
-                    }
+                for (int vq = 0; vq < 4; ++vq) {
+                    bf16_t *pos = st + (wm + i * 32 + (lane & 31)) * CLD + wn + j * 32 + vq * 8 + (lane >> 5) * 4;
+                    f32x4 v = {acc[i][j][vq * 4], acc[i][j][vq * 4 + 1], acc[i][j][vq * 4 + 2], acc[i][j][vq * 4 + 3]};
+                    fn(pos, v);
                 }
-            }
+    };
+    auto put4 = [](bf16_t *pos, const f32x4 &v) {
+        bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+        *(bf16x4 *)pos = o;
+    };
+    auto flush = [&](bf16_t *out) {
+        __syncthreads();
+#pragma unroll
+        for (int p = 0; p < 16; ++p) {
+            const int row = (tid >> 5) + 16 * p, gm = m0 + row, gn = n0 + (tid & 31) * 8;
+            const u32x4 v = *(const u32x4 *)(st + row * CLD + (tid & 31) * 8);
+            if (gm < Me && gn < d.N) *(u32x4 *)(out + (int64_t)gm * d.ldc + gn) = v;
         }
+    };
+    if (EPI == EPI_STORE) {
+        for_each_quad([&](bf16_t *pos, const f32x4 &v) { put4(pos, v); });
+        flush(C);
+    } else if (EPI == EPI_GELU) {
+        if (d.C2) {
+            for_each_quad([&](bf16_t *pos, const f32x4 &v) { put4(pos, v); });
+            flush((bf16_t *)d.C2 + (int64_t)e * d.strideC);
+            __syncthreads();
+        }
+        for_each_quad([&](bf16_t *pos, const f32x4 &v) {
+            f32x4 g = {gelu_fast(v[0], act), gelu_fast(v[1], act), gelu_fast(v[2], act), gelu_fast(v[3], act)};
+            put4(pos, g);
+        });
+        flush(C);
+    } else {
+        const bf16_t *Zin = (const bf16_t *)d.Zin + (int64_t)e * d.strideC;
+#pragma unroll
+        for (int p = 0; p < 16; ++p) {
+            const int row = (tid >> 5) + 16 * p, gm = m0 + row, gn = n0 + (tid & 31) * 8;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (gm < Me && gn < d.N) v = *(const u32x4 *)(Zin + (int64_t)gm * d.ldc + gn);
+            *(u32x4 *)(st + row * CLD + (tid & 31) * 8) = v;
+        }
+        __syncthreads();
+        for_each_quad([&](bf16_t *pos, const f32x4 &v) {
+            const bf16x4 z = *(const bf16x4 *)pos;
+            f32x4 g = {v[0] * gelu_grad_fast((float)z[0], act), v[1] * gelu_grad_fast((float)z[1], act),
+                       v[2] * gelu_grad_fast((float)z[2], act), v[3] * gelu_grad_fast((float)z[3], act)};
+            put4(pos, g);
+        });
+        flush(C);
+    }
 }
 
 template <bool AXC, bool BXC>
