@@ -3,26 +3,38 @@
 // fused GeLU', dD = dZ W1^T) and weight gradients (dW = A^T B over the kept rows).
 //
 // One workgroup of 512 threads (8 waves, 2 x 4) owns a 256 x 256 output tile of one expert and
-// walks K in steps of 64 through two LDS stages (global -> registers -> LDS, one barrier per
-// step).  Each wave owns 128 x 64 of the tile: 4 x 2 MFMA blocks of 32 x 32.
+// walks K in steps of 64 through two 64 KB LDS stages.  Each wave owns 128 x 64 of the tile:
+// 4 x 2 MFMA blocks of 32 x 32.  Global data goes straight into LDS (buffer_load ... lds, 16
+// bytes per lane, no register staging); out-of-range lanes deliver zeros, so ragged row counts
+// and K tails need no branches.
 //
 // Operands are taken in the layout the layer stores them in, so no transposed copy is ever made:
-//   "KC" operand: the reduction index is contiguous in memory  -> LDS tile [256][64], 16-byte
+//   "KC" operand: the reduction index is contiguous in memory  -> LDS tile [256 x][64 k], 16-byte
 //                 LDS reads deliver 8 consecutive k to a lane directly;
-//   "XC" operand: the output index is contiguous in memory     -> LDS tile [64][256], read with
+//   "XC" operand: the output index is contiguous in memory     -> LDS tile [64 k][256 x], read with
 //                 the LDS transpose load (ds_read_b64_tr_b16), which hands lane i of a 16-lane
 //                 group the i-th column of a 4 x 16 block.
+// A direct-to-LDS load writes lane L's 16 bytes at base + 16 L, so tiles cannot be padded; bank
+// conflicts are avoided by XOR-swizzling the 16-byte granules inside each row instead:
+//   KC: granule g of row r sits at position g ^ ((r >> 1) & 7)   (rows are 128 bytes)
+//   XC: granule g of k-row k sits at position g ^ ((k & 3) << 2) (k-rows are 512 bytes)
 // Rows beyond kept[e] are never read (loaded as zero) and never written.
 #include "moe_common.h"
 
+#ifndef MOE_GEMM_DBG
+#define MOE_GEMM_DBG 0     // timing experiments only (non-zero variants compute wrong results)
+#endif
+
 namespace moe {
 
+constexpr int DBG = MOE_GEMM_DBG;
 constexpr int BM = 256, BN = 256, BK = 64, GEMM_THREADS = 512;
-constexpr int KC_LD = BK + 8;         // 144-byte rows: 16 consecutive rows hit 16 distinct 16-byte bank groups
-constexpr int XC_LD = 256 + 32;       // 576-byte k-rows: 4 consecutive k-rows land in 4 distinct 64-byte quarters
-constexpr int STAGE_ELEMS = 256 * KC_LD;   // == 64 * XC_LD
-static_assert(256 * KC_LD == 64 * XC_LD, "both tile shapes share one stage size");
+constexpr int OPER_BYTES = 256 * 64 * 2;       // one operand's k-tile
+constexpr int STAGE_BYTES = 2 * OPER_BYTES;
+constexpr int CLD = BN + 8;                    // epilogue staging row (elements)
+constexpr int SMEM_BYTES = BM * CLD * 2 > 2 * STAGE_BYTES ? BM * CLD * 2 : 2 * STAGE_BYTES;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((address_space(3))) void lds_void;
 
 // GeLU for the bf16 epilogues: erf by the Abramowitz-Stegun 7.1.26 rational form (absolute error
 // 1.5e-7, far below bf16 resolution) with hardware exp and reciprocal; no branches.
@@ -60,83 +72,103 @@ __device__ __forceinline__ float gelu_grad_fast(float x, int act) {
     return 0.5f * (1.0f + copysignf(er, x)) + x * ex * 0.3989422804014327f;
 }
 
-struct TileLoader {
-    u32x4 r[4];
-};
-
-// Buffer resource over one expert's operand: loads beyond `bytes` (and lanes whose offset is forced
-// out of range) return zero without a branch.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+// Buffer resource (raw, stride 0) over one expert's operand: lanes whose byte offset is not below
+// `bytes` -- including offsets forced to OOB -- deliver zero without a branch.
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+__device__ __forceinline__ i32x4 make_rsrc(const void *p, uint32_t bytes) {
+    const uint64_t a = (uint64_t)p;
+    i32x4 r;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+    r[1] = __builtin_amdgcn_readfirstlane((int)((uint32_t)(a >> 32) & 0xffffu));
+    r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+    r[3] = 0x00020000;
+    return r;
 }
 constexpr uint32_t OOB = 0x80000000u;
 
-// global -> registers for one operand's k-tile.  xc: tile is [64 k][256 x]; else [256 x][64 k].
-// xoff[p] is the byte offset of this thread's p-th 16-byte piece at k = 0 (already out of range
-// when its row/column lies outside the operand); the k part is added per tile.
+// One direct global -> LDS load: lane L's 16 bytes land at LDS byte address lds_addr + 16 L.
+// Written as inline assembly so that the compiler does not order later LDS reads of the *other*
+// stage behind it; completion is awaited explicitly (s_waitcnt vmcnt) before the stage is read.
+__device__ __forceinline__ void load_to_lds(const i32x4 &rsrc, uint32_t lds_addr, uint32_t voff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(rsrc)
+                 : "memory", "m0");
+}
+
+// Per-thread state of the global -> LDS copy of one operand.  A wave copies chunks 4*wave .. +3
+// of the tile's 32 one-KB chunks; lane L fills granule L of the chunk.
+struct Loader {
+    uint32_t off[4];    // byte offset of this lane's granule at k-tile 0 (OOB if outside the operand in x)
+    int32_t kthr[4];    // the granule is inside K for k-tile origin k0 iff k0 < kthr
+};
+
 template <bool XC>
-__device__ __forceinline__ void loader_init(uint32_t (&xoff)[4], int ld, int x0, int xlim, int tid) {
+__device__ __forceinline__ void loader_init(Loader &L, int ld, int x0, int xlim, int klim, int wave, int lane) {
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
+    for (int q = 0; q < 4; ++q) {
+        const int chunk = wave * 4 + q;
         if (XC) {
-            const int gx = x0 + (tid & 31) * 8;
-            const uint32_t o = ((uint32_t)((tid >> 5) + 16 * p) * ld + gx) * 2u;
-            xoff[p] = gx < xlim ? o : OOB;
+            const int krow = chunk * 2 + (lane >> 5);
+            const int g = (lane & 31) ^ ((krow & 3) << 2);
+            const int gx = x0 + g * 8;
+            L.off[q] = gx < xlim ? ((uint32_t)krow * ld + gx) * 2u : OOB;
+            L.kthr[q] = klim - krow;
         } else {
-            const int gx = x0 + (tid >> 3) + 64 * p;
-            const uint32_t o = ((uint32_t)gx * ld + (tid & 7) * 8) * 2u;
-            xoff[p] = gx < xlim ? o : OOB;
+            const int row = chunk * 8 + (lane >> 3);
+            const int g = (lane & 7) ^ ((row >> 1) & 7);
+            const int gx = x0 + row;
+            L.off[q] = gx < xlim ? ((uint32_t)gx * ld + g * 8) * 2u : OOB;
+            L.kthr[q] = klim - g * 8;
         }
     }
 }
 
 template <bool XC>
-__device__ __forceinline__ void load_tile(TileLoader &t, __amdgpu_buffer_rsrc_t rsrc, const uint32_t (&xoff)[4],
-                                          int ld, int k0, int klim, int tid) {
+__device__ __forceinline__ void issue_loads(const i32x4 &rsrc, const Loader &L, int ld, int k0, uint32_t dst,
+                                            int wave) {
+    const uint32_t kadd = XC ? (uint32_t)k0 * ld * 2u : (uint32_t)k0 * 2u;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        uint32_t off;
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t voff = k0 < L.kthr[q] ? L.off[q] + kadd : OOB;
+        load_to_lds(rsrc, dst + (uint32_t)(wave * 4 + q) * 1024u, voff);
+    }
+}
+
+// Byte offsets (inside an operand tile) from which lane `lane` reads its MFMA fragments.
+//   KC: one offset per k-step (4), blocks of 32 rows add 32*128 bytes.
+//   XC: one offset per 32-column block, k-steps add 16*512 bytes, the second half 4*512.
+template <bool XC, int NBLK>
+struct FragAddr {
+    int32_t a[XC ? NBLK : 4];
+    __device__ __forceinline__ void init(int xbase, int lane) {
         if (XC) {
-            const int gk = k0 + (tid >> 5) + 16 * p;
-            off = gk < klim ? xoff[p] + (uint32_t)k0 * ld * 2u : OOB;
-        } else {
-            const int gk = k0 + (tid & 7) * 8;
-            off = gk < klim ? xoff[p] + (uint32_t)k0 * 2u : OOB;
-        }
-        t.r[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, 0);
-    }
-}
-
-template <bool XC>
-__device__ __forceinline__ void store_tile(const TileLoader &t, bf16_t *stage, int tid) {
+            const int s = (lane >> 2) & 3;
+            const int kr = 8 * (lane >> 5) + ((lane & 15) >> 2);
+            const int glow = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        int off;
-        if (XC)
-            off = ((tid >> 5) + 16 * p) * XC_LD + (tid & 31) * 8;
-        else
-            off = ((tid >> 3) + 64 * p) * KC_LD + (tid & 7) * 8;
-        *(u32x4 *)(stage + off) = t.r[p];
+            for (int b = 0; b < NBLK; ++b)
+                a[b] = kr * 512 + (((((xbase + b * 32) >> 3) ^ (s << 2)) + glow) << 4) + (lane & 1) * 8;
+        } else {
+            const int s = (lane >> 1) & 7;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+                a[ks] = (xbase + (lane & 31)) * 128 + (((ks * 2 + (lane >> 5)) ^ s) << 4);
+        }
     }
-}
-
-// One 32 x 16 (x by k) MFMA operand fragment for lane `lane`: 8 k values of row/column x = xb + lane%32.
-template <bool XC>
-__device__ __forceinline__ bf16x8 read_frag(const bf16_t *stage, int xb, int ks, int lane) {
-    if (XC) {
-        int x = xb + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-        int kr = ks * 16 + 8 * (lane >> 5) + ((lane & 15) >> 2);
-        const bf16_t *p0 = stage + kr * XC_LD + x;
-        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p0));
-        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p0 + 4 * XC_LD));
-        typedef __attribute__((ext_vector_type(8))) short s16x8;
-        s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        return __builtin_bit_cast(bf16x8, both);
-    } else {
-        const bf16_t *p = stage + (xb + (lane & 31)) * KC_LD + ks * 16 + (lane >> 5) * 8;
-        return *(const bf16x8 *)p;
+    __device__ __forceinline__ bf16x8 read(const char *tile, int blk, int ks) const {
+        if (XC) {
+            const char *p = tile + a[blk] + ks * 16 * 512;
+            s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p));
+            s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * 512));
+            typedef __attribute__((ext_vector_type(8))) short s16x8;
+            s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            return __builtin_bit_cast(bf16x8, both);
+        } else {
+            return *(const bf16x8 *)(tile + a[ks] + blk * 32 * 128);
+        }
     }
-}
+};
 
 template <bool AXC, bool BXC, int EPI>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int mt, int nt) {
@@ -160,11 +192,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
     // extent of this expert's operands in bytes (rows x row length)
     const uint32_t a_bytes = (uint32_t)(AXC ? Ke : Me) * (uint32_t)d.lda * 2u;
     const uint32_t b_bytes = (uint32_t)(BXC ? Ke : d.N) * (uint32_t)d.ldb * 2u;
-    const __amdgpu_buffer_rsrc_t A = make_rsrc(Ap, a_bytes), B = make_rsrc(Bp, b_bytes);
+    const i32x4 A = make_rsrc(Ap, a_bytes), B = make_rsrc(Bp, b_bytes);
 
-    __shared__ __attribute__((aligned(16))) bf16_t lds[2][2][STAGE_ELEMS];
+    __shared__ __attribute__((aligned(1024))) char smem[SMEM_BYTES];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t smem_addr = (uint32_t)(uintptr_t)(lds_void *)smem;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = (wave >> 2) * 128, wn = (wave & 3) * 64;
 
     f32x16 acc[4][2];
@@ -177,19 +211,23 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
 
     const int nk = (Ke + BK - 1) / BK;
     // Software pipeline.  Per k-tile and wave: 4 k-steps of 8 MFMAs.  Fragments are double
-    // buffered (F0/F1) so every LDS read is issued one k-step (8 MFMAs) before its use; the next
-    // tile's global data sits in registers (ta/tb) for a whole tile before it is written to the
-    // other LDS stage.  Loads past K return zero (buffer bounds), so the loop body has no branches.
+    // buffered (a0/b0, a1/b1) so every LDS read is issued one k-step (8 MFMAs) before its use.
+    // Tile kt+2 is requested into the stage tile kt was read from, right after the barrier that
+    // ends those reads, and has a whole k-tile of MFMAs to arrive.
     bf16x8 a0[4], b0[2], a1[4], b1[2];
-    TileLoader ta, tb;
-    uint32_t xa[4], xb[4];
-    loader_init<AXC>(xa, d.lda, m0, Me, tid);
-    loader_init<BXC>(xb, d.ldb, n0, d.N, tid);
+    Loader la, lb;
+    loader_init<AXC>(la, d.lda, m0, Me, Ke, wave, lane);
+    loader_init<BXC>(lb, d.ldb, n0, d.N, Ke, wave, lane);
+    FragAddr<AXC, 4> fa;
+    FragAddr<BXC, 2> fb;
+    fa.init(wm, lane);
+    fb.init(wn, lane);
     auto rd = [&](bf16x8(&af)[4], bf16x8(&bf)[2], int stage, int ks) {
+        const char *ta = smem + stage * STAGE_BYTES, *tb = ta + OPER_BYTES;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) af[i] = read_frag<AXC>(lds[stage][0], wm + i * 32, ks, lane);
+        for (int i = 0; i < 4; ++i) af[i] = fa.read(ta, i, ks);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) bf[j] = read_frag<BXC>(lds[stage][1], wn + j * 32, ks, lane);
+        for (int j = 0; j < 2; ++j) bf[j] = fb.read(tb, j, ks);
     };
     auto mma = [&](const bf16x8(&af)[4], const bf16x8(&bf)[2]) {
 #pragma unroll
@@ -198,13 +236,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
             for (int j = 0; j < 2; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], af[i], acc[i][j], 0, 0, 0);
     };
+    auto request = [&](int kt, int stage) {
+        issue_loads<AXC>(A, la, d.lda, kt * BK, smem_addr + stage * STAGE_BYTES, wave);
+        issue_loads<BXC>(B, lb, d.ldb, kt * BK, smem_addr + stage * STAGE_BYTES + OPER_BYTES, wave);
+    };
     if (nk > 0) {
-        load_tile<AXC>(ta, A, xa, d.lda, 0, Ke, tid);
-        load_tile<BXC>(tb, B, xb, d.ldb, 0, Ke, tid);
-        store_tile<AXC>(ta, lds[0][0], tid);
-        store_tile<BXC>(tb, lds[0][1], tid);
-        load_tile<AXC>(ta, A, xa, d.lda, BK, Ke, tid);
-        load_tile<BXC>(tb, B, xb, d.ldb, BK, Ke, tid);
+        request(0, 0);
+        request(1, 1);
+        __builtin_amdgcn_s_waitcnt(0x0F78);      // vmcnt(8): tile 0 has landed, tile 1 may be in flight
         __syncthreads();
         rd(a0, b0, 0, 0);
     }
@@ -219,25 +258,21 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
         mma(a1, b1);
         __builtin_amdgcn_sched_barrier(0);
         rd(a1, b1, cur, 3);
-        store_tile<AXC>(ta, lds[cur ^ 1][0], tid);
-        store_tile<BXC>(tb, lds[cur ^ 1][1], tid);
-        load_tile<AXC>(ta, A, xa, d.lda, (kt + 2) * BK, Ke, tid);
-        load_tile<BXC>(tb, B, xb, d.ldb, (kt + 2) * BK, Ke, tid);
-        mma(a0, b0);
-        // interleave: one MFMA, one LDS write of the staged tile, one global load of the tile after it
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        }
         __builtin_amdgcn_sched_barrier(0);
+        mma(a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        // tile kt+1 (requested one k-tile ago) must have landed, and this wave's reads of stage
+        // `cur` must be complete before anyone overwrites it
+        __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0) lgkmcnt(0)
         __syncthreads();
+        if (DBG != 1) request(DBG == 4 ? 0 : kt + 2, cur);
         rd(a0, b0, cur ^ 1, 0);
         __builtin_amdgcn_sched_barrier(0);
         mma(a1, b1);
         __builtin_amdgcn_sched_barrier(0);
     }
+    __builtin_amdgcn_s_waitcnt(0x0070);          // nothing may still be writing LDS when it is reused
+    __syncthreads();
 
     // Epilogue.  The MFMAs were issued with the operands swapped (B fragment first), so the
     // accumulators hold the transposed block: lane owns output row m = lane%32 and, per group of
@@ -245,9 +280,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
     // converted to bf16, staged in LDS (the operand stages are free now; reads still in flight
     // from the loop's last prefetch are never used) and written out as full 512-byte rows.
     bf16_t *C = (bf16_t *)d.C + (int64_t)e * d.strideC;
-    bf16_t *st = &lds[0][0][0];
-    constexpr int CLD = BN + 8;
-    static_assert(BM * CLD <= 4 * STAGE_ELEMS, "staging tile fits in the operand stages");
+    bf16_t *st = (bf16_t *)smem;
     const int act = d.act;
     auto for_each_quad = [&](auto fn) {
 #pragma unroll
