@@ -28,11 +28,12 @@
 namespace moe {
 
 constexpr int DBG = MOE_GEMM_DBG;
-constexpr int BM = 256, BN = 256, BK = 64, GEMM_THREADS = 512;
-constexpr int OPER_BYTES = 256 * 64 * 2;       // one operand's k-tile
+constexpr int BM = 256, BN = 256, BK = 32, GEMM_THREADS = 512;
+constexpr int NSTAGE = 4;                      // LDS stages; tiles are requested NSTAGE-1 k-tiles ahead
+constexpr int OPER_BYTES = 256 * BK * 2;       // one operand's k-tile (16 KB)
 constexpr int STAGE_BYTES = 2 * OPER_BYTES;
 constexpr int CLD = BN + 8;                    // epilogue staging row (elements)
-constexpr int SMEM_BYTES = BM * CLD * 2 > 2 * STAGE_BYTES ? BM * CLD * 2 : 2 * STAGE_BYTES;
+constexpr int SMEM_BYTES = BM * CLD * 2 > NSTAGE * STAGE_BYTES ? BM * CLD * 2 : NSTAGE * STAGE_BYTES;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((address_space(3))) void lds_void;
 
@@ -96,18 +97,20 @@ __device__ __forceinline__ void load_to_lds(const i32x4 &rsrc, uint32_t lds_addr
                  : "memory", "m0");
 }
 
-// Per-thread state of the global -> LDS copy of one operand.  A wave copies chunks 4*wave .. +3
-// of the tile's 32 one-KB chunks; lane L fills granule L of the chunk.
+// Per-thread state of the global -> LDS copy of one operand.  A wave copies chunks 2*wave, 2*wave+1
+// of the tile's 16 one-KB chunks; lane L fills granule L of the chunk.
+//   KC chunk: 16 rows x 64 bytes, lane L -> row L/4, position L%4
+//   XC chunk: 2 k-rows x 512 bytes, lane L -> k-row L/32, position L%32
 struct Loader {
-    uint32_t off[4];    // byte offset of this lane's granule at k-tile 0 (OOB if outside the operand in x)
-    int32_t kthr[4];    // the granule is inside K for k-tile origin k0 iff k0 < kthr
+    uint32_t off[2];    // byte offset of this lane's granule at k-tile 0 (OOB if outside the operand in x)
+    int32_t kthr[2];    // the granule is inside K for k-tile origin k0 iff k0 < kthr
 };
 
 template <bool XC>
 __device__ __forceinline__ void loader_init(Loader &L, int ld, int x0, int xlim, int klim, int wave, int lane) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int chunk = wave * 4 + q;
+    for (int q = 0; q < 2; ++q) {
+        const int chunk = wave * 2 + q;
         if (XC) {
             const int krow = chunk * 2 + (lane >> 5);
             const int g = (lane & 31) ^ ((krow & 3) << 2);
@@ -115,8 +118,8 @@ __device__ __forceinline__ void loader_init(Loader &L, int ld, int x0, int xlim,
             L.off[q] = gx < xlim ? ((uint32_t)krow * ld + gx) * 2u : OOB;
             L.kthr[q] = klim - krow;
         } else {
-            const int row = chunk * 8 + (lane >> 3);
-            const int g = (lane & 7) ^ ((row >> 1) & 7);
+            const int row = chunk * 16 + (lane >> 2);
+            const int g = (lane & 3) ^ ((row >> 2) & 3);
             const int gx = x0 + row;
             L.off[q] = gx < xlim ? ((uint32_t)gx * ld + g * 8) * 2u : OOB;
             L.kthr[q] = klim - g * 8;
@@ -129,18 +132,18 @@ __device__ __forceinline__ void issue_loads(const i32x4 &rsrc, const Loader &L, 
                                             int wave) {
     const uint32_t kadd = XC ? (uint32_t)k0 * ld * 2u : (uint32_t)k0 * 2u;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+    for (int q = 0; q < 2; ++q) {
         const uint32_t voff = k0 < L.kthr[q] ? L.off[q] + kadd : OOB;
-        load_to_lds(rsrc, dst + (uint32_t)(wave * 4 + q) * 1024u, voff);
+        load_to_lds(rsrc, dst + (uint32_t)(wave * 2 + q) * 1024u, voff);
     }
 }
 
 // Byte offsets (inside an operand tile) from which lane `lane` reads its MFMA fragments.
-//   KC: one offset per k-step (4), blocks of 32 rows add 32*128 bytes.
+//   KC: one offset per k-step (2), blocks of 32 rows add 32*64 bytes.
 //   XC: one offset per 32-column block, k-steps add 16*512 bytes, the second half 4*512.
 template <bool XC, int NBLK>
 struct FragAddr {
-    int32_t a[XC ? NBLK : 4];
+    int32_t a[XC ? NBLK : 2];
     __device__ __forceinline__ void init(int xbase, int lane) {
         if (XC) {
             const int s = (lane >> 2) & 3;
@@ -150,10 +153,10 @@ struct FragAddr {
             for (int b = 0; b < NBLK; ++b)
                 a[b] = kr * 512 + (((((xbase + b * 32) >> 3) ^ (s << 2)) + glow) << 4) + (lane & 1) * 8;
         } else {
-            const int s = (lane >> 1) & 7;
+            const int s = (lane >> 2) & 3;        // ((row >> 2) & 3) with row = xbase + lane%32, xbase % 32 == 0
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-                a[ks] = (xbase + (lane & 31)) * 128 + (((ks * 2 + (lane >> 5)) ^ s) << 4);
+            for (int ks = 0; ks < 2; ++ks)
+                a[ks] = (xbase + (lane & 31)) * 64 + (((ks * 2 + (lane >> 5)) ^ s) << 4);
         }
     }
     __device__ __forceinline__ bf16x8 read(const char *tile, int blk, int ks) const {
@@ -165,7 +168,7 @@ struct FragAddr {
             s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             return __builtin_bit_cast(bf16x8, both);
         } else {
-            return *(const bf16x8 *)(tile + a[ks] + blk * 32 * 128);
+            return *(const bf16x8 *)(tile + a[ks] + blk * 32 * 64);
         }
     }
 };
@@ -210,10 +213,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     const int nk = (Ke + BK - 1) / BK;
-    // Software pipeline.  Per k-tile and wave: 4 k-steps of 8 MFMAs.  Fragments are double
-    // buffered (a0/b0, a1/b1) so every LDS read is issued one k-step (8 MFMAs) before its use.
-    // Tile kt+2 is requested into the stage tile kt was read from, right after the barrier that
-    // ends those reads, and has a whole k-tile of MFMAs to arrive.
+    // Software pipeline.  A k-tile is 32 deep: 2 k-steps of 8 MFMAs per wave.  Tile kt lives in
+    // stage kt % NSTAGE and is requested NSTAGE-1 iterations before it is consumed, so up to
+    // (NSTAGE-1) x 32 KB are in flight per workgroup; that, not the MFMA rate, is what bounds this
+    // kernel when HBM latency is exposed.  Fragments alternate between two register sets so that
+    // every LDS read is issued one k-step (8 MFMAs) before its use.
     bf16x8 a0[4], b0[2], a1[4], b1[2];
     Loader la, lb;
     loader_init<AXC>(la, d.lda, m0, Me, Ke, wave, lane);
@@ -223,6 +227,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
     fa.init(wm, lane);
     fb.init(wn, lane);
     auto rd = [&](bf16x8(&af)[4], bf16x8(&bf)[2], int stage, int ks) {
+        if (DBG == 5 || DBG == 6) return;
         const char *ta = smem + stage * STAGE_BYTES, *tb = ta + OPER_BYTES;
 #pragma unroll
         for (int i = 0; i < 4; ++i) af[i] = fa.read(ta, i, ks);
@@ -240,38 +245,35 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
         issue_loads<AXC>(A, la, d.lda, kt * BK, smem_addr + stage * STAGE_BYTES, wave);
         issue_loads<BXC>(B, lb, d.ldb, kt * BK, smem_addr + stage * STAGE_BYTES + OPER_BYTES, wave);
     };
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a1[i] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < 2; ++j) b1[j] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
     if (nk > 0) {
-        request(0, 0);
-        request(1, 1);
-        __builtin_amdgcn_s_waitcnt(0x0F78);      // vmcnt(8): tile 0 has landed, tile 1 may be in flight
-        __syncthreads();
-        rd(a0, b0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < NSTAGE - 1; ++t) request(t, t);
     }
+    int stage = 0;                                   // kt % NSTAGE
     for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        rd(a1, b1, cur, 1);
+        // tile kt has landed once at most the (NSTAGE-2) newer requests of 4 loads each are
+        // outstanding; this wave's reads of tile kt-1 must be complete before its stage is reused
+        static_assert(NSTAGE == 4, "the wait count below is 4 * (NSTAGE - 2)");
+        __builtin_amdgcn_s_waitcnt(0x0078);          // vmcnt(8) lgkmcnt(0)
+        if (DBG != 6 && DBG != 7) __syncthreads();
+        const int prev = stage == 0 ? NSTAGE - 1 : stage - 1;
+        if (DBG != 1 && DBG < 5) request(kt + NSTAGE - 1, prev);
+        rd(a0, b0, stage, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(a1, b1);                                 // second k-step of tile kt-1
+        __builtin_amdgcn_sched_barrier(0);
+        rd(a1, b1, stage, 1);
         __builtin_amdgcn_sched_barrier(0);
         mma(a0, b0);
         __builtin_amdgcn_sched_barrier(0);
-        rd(a0, b0, cur, 2);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
-        rd(a1, b1, cur, 3);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(a0, b0);
-        __builtin_amdgcn_sched_barrier(0);
-        // tile kt+1 (requested one k-tile ago) must have landed, and this wave's reads of stage
-        // `cur` must be complete before anyone overwrites it
-        __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0) lgkmcnt(0)
-        __syncthreads();
-        if (DBG != 1) request(DBG == 4 ? 0 : kt + 2, cur);
-        rd(a0, b0, cur ^ 1, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
+        stage = stage == NSTAGE - 1 ? 0 : stage + 1;
     }
-    __builtin_amdgcn_s_waitcnt(0x0070);          // nothing may still be writing LDS when it is reused
+    mma(a1, b1);
+    __builtin_amdgcn_s_waitcnt(0x0070);              // nothing may still be writing LDS when it is reused
     __syncthreads();
 
     // Epilogue.  The MFMAs were issued with the operands swapped (B fragment first), so the
