@@ -19,6 +19,7 @@
 //   KC: granule g of row r sits at position g ^ ((r >> 1) & 7)   (rows are 128 bytes)
 //   XC: granule g of k-row k sits at position g ^ ((k & 3) << 2) (k-rows are 512 bytes)
 // Rows beyond kept[e] are never read (loaded as zero) and never written.
+#include <type_traits>
 #include "moe_common.h"
 
 #ifndef MOE_GEMM_DBG
@@ -29,6 +30,7 @@ namespace moe {
 
 constexpr int DBG = MOE_GEMM_DBG;
 constexpr int BM = 256, BN = 256, BK = 32, GEMM_THREADS = 512;
+constexpr int LIGHT_ROWS = 128;                 // a last m-tile with at most this many rows is scheduled as "light"
 constexpr int NSTAGE = 4;                      // LDS stages; tiles are requested NSTAGE-1 k-tiles ahead
 constexpr int OPER_BYTES = 256 * BK * 2;       // one operand's k-tile (16 KB)
 constexpr int STAGE_BYTES = 2 * OPER_BYTES;
@@ -134,6 +136,10 @@ __device__ __forceinline__ void issue_loads(const i32x4 &rsrc, const Loader &L, 
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
         const uint32_t voff = k0 < L.kthr[q] ? L.off[q] + kadd : OOB;
+        if (DBG == 9) {
+            u32x4 dummy;
+            asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(dummy) : "v"(voff), "s"(rsrc) : "memory");
+        } else
         load_to_lds(rsrc, dst + (uint32_t)(wave * 2 + q) * 1024u, voff);
     }
 }
@@ -175,20 +181,77 @@ struct FragAddr {
 
 template <bool AXC, bool BXC, int EPI>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int mt, int nt) {
-    // XCD-aware order: consecutive workgroup ids go round-robin over the 8 XCDs, so give every
-    // XCD one contiguous range of logical tiles (tiles that share a weight panel share an L2).
-    const int nwg = gridDim.x, pid = blockIdx.x;
-    const int xcd = pid & 7, per = nwg >> 3, rem = nwg & 7;
-    const int logical = xcd * per + (xcd < rem ? xcd : rem) + (pid >> 3);
-    const int e = logical / (mt * nt);
-    const int rr = logical - e * (mt * nt);
-    const int nti = rr / mt, mti = rr - nti * mt;     // m fastest: the m-tiles of one weight panel run together
+    // Tile schedule.  Tiles are "heavy" (a full 256-row tile, or a last tile with more than
+    // LIGHT_ROWS valid rows) or "light" (a last tile with at most LIGHT_ROWS valid rows, in which
+    // whole 32-row MFMA blocks are skipped).  Consecutive workgroup ids go round-robin over the 8
+    // XCDs, so XCD x takes the x-th eighth of the heavy list (tiles that share a weight panel then
+    // share an L2) and, after those, the x-th eighth of the light list: the cheap tiles fill the
+    // last, partial round of the grid instead of idling compute units.  kept[] lives on the
+    // device, so every workgroup derives the lists itself with a short scalar scan over experts.
+    const int pid = blockIdx.x;
+    const int xcd = pid & 7, local = pid >> 3;
+    const int lane_s = threadIdx.x & 63;
+    // per-expert tile counts, 64 experts at a time: lane x of a chunk holds expert chunk*64 + x
+    auto counts_of = [&](int x, int &hv, int &lt) {
+        const int Mx = x < d.E ? (d.rows_from_kept ? d.kept[x] : d.M) : 0;
+        const int remx = Mx % BM;
+        hv = Mx / BM + (remx > LIGHT_ROWS ? 1 : 0);
+        lt = (remx > 0 && remx <= LIGHT_ROWS) ? 1 : 0;
+    };
+    auto wave_sum = [&](int v) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+        return v;
+    };
+    auto wave_incl_scan = [&](int v) {
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(v, o);
+            if (lane_s >= o) v += t;
+        }
+        return v;
+    };
+    int nH = 0, nL = 0;
+    for (int c = 0; c < d.E; c += 64) {
+        int hv, lt;
+        counts_of(c + lane_s, hv, lt);
+        nH += wave_sum(hv);
+        nL += wave_sum(lt);
+    }
+    nH *= nt;
+    nL *= nt;
+    const int startH = (int)(((int64_t)xcd * nH) >> 3), cntH = (int)(((int64_t)(xcd + 1) * nH) >> 3) - startH;
+    const int startL = (int)(((int64_t)xcd * nL) >> 3), cntL = (int)(((int64_t)(xcd + 1) * nL) >> 3) - startL;
+    const bool light = local >= cntH;
+    if (light && local - cntH >= cntL) return;
+    int idx = light ? startL + local - cntH : startH + local;     // position in the heavy / light list
+    int e = 0, mti = 0, nti = 0;
+    for (int c = 0; c < d.E; c += 64) {
+        int hv, lt;
+        counts_of(c + lane_s, hv, lt);
+        const int mine = (light ? lt : hv) * nt;
+        const int incl = wave_incl_scan(mine);
+        const unsigned long long hit = __ballot(idx < incl);
+        if (hit) {
+            const int src = __ffsll((long long)hit) - 1;
+            e = c + src;
+            const int r = idx - __shfl(incl - mine, src);
+            const int hve = __shfl(hv, src);
+            if (light) { nti = r; mti = hve; }
+            else { nti = r / hve; mti = r - nti * hve; }   // m fastest: the m-tiles of one weight panel run together
+            break;
+        }
+        idx -= __shfl(incl, 63);
+    }
+    e = __builtin_amdgcn_readfirstlane(e);
+    mti = __builtin_amdgcn_readfirstlane(mti);
+    nti = __builtin_amdgcn_readfirstlane(nti);
+    (void)mt;
 
     const int kept = d.kept[e];
     const int Me = d.rows_from_kept ? kept : d.M;
     const int Ke = d.rows_from_kept ? d.K : kept;
     const int m0 = mti * BM, n0 = nti * BN;
-    if (m0 >= Me) return;
 
     const bf16_t *Ap = (const bf16_t *)d.A + (int64_t)e * d.strideA;
     const bf16_t *Bp = (const bf16_t *)d.B + (int64_t)e * d.strideB;
@@ -226,20 +289,28 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
     FragAddr<BXC, 2> fb;
     fa.init(wm, lane);
     fb.init(wn, lane);
-    auto rd = [&](bf16x8(&af)[4], bf16x8(&bf)[2], int stage, int ks) {
+    // 32-row blocks of this wave that hold valid rows (4 except in a last, partial m-tile)
+    const int rv = Me - m0 - wm;
+    const int nvi = __builtin_amdgcn_readfirstlane(rv >= 128 ? 4 : (rv <= 0 ? 0 : (rv + 31) >> 5));
+    auto rd = [&](bf16x8(&af)[4], bf16x8(&bf)[2], int stage, int ks, auto full) {
         if (DBG == 5 || DBG == 6) return;
         const char *ta = smem + stage * STAGE_BYTES, *tb = ta + OPER_BYTES;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) af[i] = fa.read(ta, i, ks);
+        for (int i = 0; i < 4; ++i)
+            if (decltype(full)::value || i < nvi) af[i] = fa.read(ta, i, ks);
+        if (decltype(full)::value || nvi > 0) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) bf[j] = fb.read(tb, j, ks);
+            for (int j = 0; j < 2; ++j) bf[j] = fb.read(tb, j, ks);
+        }
     };
-    auto mma = [&](const bf16x8(&af)[4], const bf16x8(&bf)[2]) {
+    auto mma = [&](const bf16x8(&af)[4], const bf16x8(&bf)[2], auto full) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
+            if (decltype(full)::value || i < nvi) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], af[i], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], af[i], acc[i][j], 0, 0, 0);
+            }
     };
     auto request = [&](int kt, int stage) {
         issue_loads<AXC>(A, la, d.lda, kt * BK, smem_addr + stage * STAGE_BYTES, wave);
@@ -249,30 +320,44 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
     for (int i = 0; i < 4; ++i) a1[i] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
     for (int j = 0; j < 2; ++j) b1[j] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    if (DBG != 0) {      // experiments: operands must look like real data (power draw depends on it)
+        for (int i = tid; i < NSTAGE * STAGE_BYTES / 4; i += GEMM_THREADS) {
+            uint32_t r = (uint32_t)i * 2654435761u + (uint32_t)pid;
+            r ^= r >> 15; r *= 2246822519u; r ^= r >> 13;
+            ((uint32_t *)smem)[i] = (r & 0x807f807fu) | 0x3c003c00u | ((r >> 3) & 0x03800380u);
+        }
+        __syncthreads();
+    }
     if (nk > 0) {
 #pragma unroll
         for (int t = 0; t < NSTAGE - 1; ++t) request(t, t);
     }
-    int stage = 0;                                   // kt % NSTAGE
-    for (int kt = 0; kt < nk; ++kt) {
-        // tile kt has landed once at most the (NSTAGE-2) newer requests of 4 loads each are
-        // outstanding; this wave's reads of tile kt-1 must be complete before its stage is reused
-        static_assert(NSTAGE == 4, "the wait count below is 4 * (NSTAGE - 2)");
-        __builtin_amdgcn_s_waitcnt(0x0078);          // vmcnt(8) lgkmcnt(0)
-        if (DBG != 6 && DBG != 7) __syncthreads();
-        const int prev = stage == 0 ? NSTAGE - 1 : stage - 1;
-        if (DBG != 1 && DBG < 5) request(kt + NSTAGE - 1, prev);
-        rd(a0, b0, stage, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(a1, b1);                                 // second k-step of tile kt-1
-        __builtin_amdgcn_sched_barrier(0);
-        rd(a1, b1, stage, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(a0, b0);
-        __builtin_amdgcn_sched_barrier(0);
-        stage = stage == NSTAGE - 1 ? 0 : stage + 1;
-    }
-    mma(a1, b1);
+    auto main_loop = [&](auto full) {
+        int stage = 0;                               // kt % NSTAGE
+        for (int kt = 0; kt < nk; ++kt) {
+            // tile kt has landed once at most the (NSTAGE-2) newer requests of 4 loads each are
+            // outstanding; this wave's reads of tile kt-1 must be complete before its stage is reused
+            static_assert(NSTAGE == 4, "the wait count below is 4 * (NSTAGE - 2)");
+            __builtin_amdgcn_s_waitcnt(0x0078);      // vmcnt(8) lgkmcnt(0)
+            if (DBG != 6 && DBG != 7) __syncthreads();
+            const int prev = stage == 0 ? NSTAGE - 1 : stage - 1;
+            if (DBG != 1 && DBG < 5) request(kt + NSTAGE - 1, prev);
+            rd(a0, b0, stage, 0, full);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(a1, b1, full);                       // second k-step of tile kt-1
+            __builtin_amdgcn_sched_barrier(0);
+            rd(a1, b1, stage, 1, full);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(a0, b0, full);
+            __builtin_amdgcn_sched_barrier(0);
+            stage = stage == NSTAGE - 1 ? 0 : stage + 1;
+        }
+        mma(a1, b1, full);
+    };
+    if (__builtin_amdgcn_readfirstlane(Me - m0 >= BM))
+        main_loop(std::true_type{});
+    else
+        main_loop(std::false_type{});
     __builtin_amdgcn_s_waitcnt(0x0070);              // nothing may still be writing LDS when it is reused
     __syncthreads();
 
@@ -345,7 +430,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
 
 template <bool AXC, bool BXC>
 static void launch_epi(const GemmDesc &d, int mt, int nt, hipStream_t s) {
-    dim3 grid((unsigned)((int64_t)d.E * mt * nt)), block(GEMM_THREADS);
+    dim3 grid((unsigned)((int64_t)d.E * mt * nt + 16)), block(GEMM_THREADS);
     switch (d.epi) {
         case EPI_STORE:
             hipLaunchKernelGGL((gemm_bf16_kernel<AXC, BXC, EPI_STORE>), grid, block, 0, s, d, mt, nt);
