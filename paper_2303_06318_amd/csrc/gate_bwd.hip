@@ -1,0 +1,391 @@
+// Gate backward: d_logits from the softmax Jacobian, d_w_gate = X^T d_logits, d_x += d_logits w_gate^T.
+#include "moe_common.h"
+
+namespace moe {
+
+// ------------------------------------------------------------------ gate backward
+// d_logits[t,j] = d_gate_p[t] * p_t * ([j == e_t] - probs[t,j])
+__global__ void gate_dlogits_kernel(const float *d_gate_p, const float *probs, const int32_t *expert, float *d_logits,
+                                    int64_t T, int E) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= T * E) return;
+    int64_t t = i / E;
+    int j = (int)(i - t * E);
+    int e = expert[t];
+    float pe = probs[t * E + e];
+    d_logits[i] = d_gate_p[t] * pe * ((j == e ? 1.f : 0.f) - probs[i]);
+}
+
+// Block = 64 columns of x (k0..k0+63) x 4 token lanes, token chunk [t0, t1).
+//   partial[chunk][k][j] = sum_{t in chunk} x[t,k] * d_logits[t,j]
+//   d_x[t,k] += sum_j d_logits[t,j] * w_gate[k,j]
+template <typename T, int EJ>
+__global__ __launch_bounds__(256) void gate_bwd_main_kernel(const T *x, const float *w_gate, const float *d_logits,
+                                                             float *partial, T *d_x, int64_t Tn, int h, int E,
+                                                             int64_t chunk_len) {
+    __shared__ float red[4][64][EJ + 1];
+    const int c = threadIdx.x & 63, tq = threadIdx.x >> 6;
+    const int k = blockIdx.x * 64 + c;
+    const bool kin = k < h;
+    const int64_t t0 = (int64_t)blockIdx.y * chunk_len;
+    const int64_t t1 = t0 + chunk_len < Tn ? t0 + chunk_len : Tn;
+    for (int j0 = 0; j0 < E; j0 += EJ) {
+        float wg[EJ], acc[EJ];
+#pragma unroll
+        for (int j = 0; j < EJ; ++j) {
+            wg[j] = (kin && j0 + j < E) ? w_gate[(int64_t)k * E + j0 + j] : 0.f;
+            acc[j] = 0.f;
+        }
+        for (int64_t t = t0 + tq; t < t1; t += 4) {
+            const float *dl = d_logits + t * E + j0;
+            const float xv = kin ? (float)x[t * h + k] : 0.f;
+            float dxa = 0.f;
+#pragma unroll
+            for (int j = 0; j < EJ; ++j) {
+                const float g = (j0 + j < E) ? dl[j] : 0.f;
+                acc[j] = fmaf(xv, g, acc[j]);
+                dxa = fmaf(g, wg[j], dxa);
+            }
+            if (d_x && kin) d_x[t * h + k] = (T)((float)d_x[t * h + k] + dxa);
+        }
+#pragma unroll
+        for (int j = 0; j < EJ; ++j) red[tq][c][j] = acc[j];
+        __syncthreads();
+        if (partial) {
+            for (int i = threadIdx.x; i < 64 * EJ; i += 256) {
+                int cc = i / EJ, j = i - cc * EJ;
+                int kk = blockIdx.x * 64 + cc;
+                if (kk < h && j0 + j < E)
+                    partial[((int64_t)blockIdx.y * h + kk) * E + j0 + j] =
+                        (red[0][cc][j] + red[1][cc][j]) + (red[2][cc][j] + red[3][cc][j]);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+__global__ void gate_dwg_reduce_kernel(const float *partial, float *d_w_gate, int64_t n, int nchunks) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    float s = 0.f;
+    for (int c = 0; c < nchunks; ++c) s += partial[(int64_t)c * n + i];
+    d_w_gate[i] = s;
+}
+
+
+// ================================================================== bf16 tokens: matrix-core path
+// d_w_gate = X^T dL is a contraction over tokens.  It runs on 16x16x32 bf16 MFMAs as
+// out^T[E, cols] = dL^T[E, tokens] X[tokens, cols]: dL keeps fp32 accuracy by being split into three
+// bf16 planes (hi + mid + lo), stored transposed [3][Epad][Tpad] so a lane's 8 consecutive tokens
+// are one 16-byte load; X tiles [32 tokens][256 cols] pass through LDS and are read with the LDS
+// transpose load.  Each workgroup owns 256 columns x one token chunk and writes a partial
+// [Epad][h] fp32 tile; a second kernel sums the chunks in a fixed order (deterministic).
+
+// d_logits and its three transposed bf16 planes.  One thread per (j, t); t is the fast index.
+__global__ void gate_dlogits_planes_kernel(const float *d_gate_p, const float *probs, const int32_t *expert,
+                                           float *d_logits, bf16_t *planes, int64_t T, int E, int Epad, int64_t Tpad) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)Epad * Tpad) return;
+    const int j = (int)(i / Tpad);
+    const int64_t t = i - (int64_t)j * Tpad;
+    float g = 0.f;
+    if (j < E && t < T) {
+        const int e = expert[t];
+        const float pe = probs[t * E + e];
+        g = d_gate_p[t] * pe * ((j == e ? 1.f : 0.f) - probs[t * E + j]);
+        d_logits[t * E + j] = g;
+    }
+    const bf16_t hi = f32_to_bf16(g);
+    const float r1 = g - bf16_to_f32(hi);
+    const bf16_t mid = f32_to_bf16(r1);
+    const bf16_t lo = f32_to_bf16(r1 - bf16_to_f32(mid));
+    const int64_t n = (int64_t)Epad * Tpad;
+    planes[i] = hi;
+    planes[n + i] = mid;
+    planes[2 * n + i] = lo;
+}
+
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4_g;
+
+// partial[chunk][e][col] = sum over the chunk's tokens of dL[t,e] * x[t,col]
+template <int NT>
+__global__ __launch_bounds__(256) void gate_dwg_mfma_kernel(const bf16_t *x, const bf16_t *planes, float *partial,
+                                                             int64_t T, int h, int64_t Tpad, int64_t chunk_len,
+                                                             int Epad) {
+    __shared__ __attribute__((aligned(16))) char xs[2][32 * 512];    // [32 tokens][256 cols] bf16, swizzled
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c0 = blockIdx.x * 256;
+    const int64_t t_begin = (int64_t)blockIdx.y * chunk_len;
+    const int64_t t_end = t_begin + chunk_len < Tpad ? t_begin + chunk_len : Tpad;
+    const int64_t plane = (int64_t)Epad * Tpad;      // distance between the hi / mid / lo planes
+
+    // loader: thread -> token rows tid/32 + 8q (q = 0..3), granule tid%32 (8 columns)
+    const int lg = tid & 31, lrow = tid >> 5;
+    const bool col_ok = c0 + lg * 8 < h;
+    u32x4 stg[4];
+    auto gload = [&](int64_t t0) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int64_t t = t0 + lrow + 8 * q;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (col_ok && t < T) v = *(const u32x4 *)(x + t * h + c0 + lg * 8);
+            stg[q] = v;
+        }
+    };
+    auto sstore = [&](int buf) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int k = lrow + 8 * q;
+            *(u32x4 *)(xs[buf] + k * 512 + ((lg ^ ((k & 3) << 2)) << 4)) = stg[q];
+        }
+    };
+    // B fragment (16 columns x 32 tokens) of column block nb for this wave: lane j%16 of token group
+    // G = lane/16 reads 8 bytes at token-row 8G + j/4 (+4), columns 4*(j%4)
+    const int kr = 8 * (lane >> 4) + ((lane & 15) >> 2), sw = (lane >> 2) & 3;
+    int boff[4];
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+        const int gran = (wave * 64 + nb * 16) / 8 + ((lane & 3) >> 1);
+        boff[nb] = kr * 512 + ((gran ^ (sw << 2)) << 4) + (lane & 1) * 8;
+    }
+    f32x4 acc[NT][4];
+#pragma unroll
+    for (int et = 0; et < NT; ++et)
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) acc[et][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    if (t_begin < t_end) {
+        gload(t_begin);
+        sstore(0);
+    }
+    __syncthreads();
+    int buf = 0;
+    for (int64_t t0 = t_begin; t0 < t_end; t0 += 32) {
+        const bool more = t0 + 32 < t_end;
+        if (more) gload(t0 + 32);
+        bf16x8 bfr[4];
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) {
+            const char *p = xs[buf] + boff[nb];
+            s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_g *)p);
+            s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_g *)(p + 4 * 512));
+            typedef __attribute__((ext_vector_type(8))) short s16x8;
+            bfr[nb] = __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        }
+#pragma unroll
+        for (int et = 0; et < NT; ++et)
+#pragma unroll
+            for (int p3 = 0; p3 < 3; ++p3) {
+                const u32x4 av = *(const u32x4 *)(planes + p3 * plane + (int64_t)(et * 16 + (lane & 15)) * Tpad + t0 +
+                                                  8 * (lane >> 4));
+                const bf16x8 a = __builtin_bit_cast(bf16x8, av);
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb)
+                    acc[et][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bfr[nb], acc[et][nb], 0, 0, 0);
+            }
+        if (more) sstore(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
+    }
+    // result block: lane holds column lane%16, rows (experts) 4*(lane/16) + v
+#pragma unroll
+    for (int et = 0; et < NT; ++et)
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) {
+            const int col = c0 + wave * 64 + nb * 16 + (lane & 15);
+            if (col < h) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int e = et * 16 + 4 * (lane >> 4) + v;
+                    partial[((int64_t)blockIdx.y * Epad + e) * h + col] = acc[et][nb][v];
+                }
+            }
+        }
+}
+
+// d_w_gate[k][j] = sum_chunks partial[chunk][j][k]
+__global__ void gate_dwg_reduce_t_kernel(const float *partial, float *d_w_gate, int h, int E, int Epad, int nchunks) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)E * h) return;
+    const int j = (int)(i / h), k = (int)(i - (int64_t)j * h);
+    float s = 0.f;
+    for (int c = 0; c < nchunks; ++c) s += partial[((int64_t)c * Epad + j) * h + k];
+    d_w_gate[(int64_t)k * E + j] = s;
+}
+
+// d_x[t, k] += sum_j dL[t,j] * w_gate[k,j].  A thread keeps CW columns x EJ experts of w_gate in
+// registers and walks the tokens of its chunk; dL rows are broadcast from LDS.
+template <int CW, int EJ>
+__global__ __launch_bounds__(256) void gate_dx_kernel(const float *w_gate, const float *d_logits, bf16_t *d_x, int64_t T,
+                                                       int h, int E, int j0, int64_t chunk_len) {
+    constexpr int TT = 64;
+    __shared__ float dl[TT][EJ];
+    const int tid = threadIdx.x;
+    const int k0 = (blockIdx.x * 256 + tid) * CW;
+    const bool kin = k0 < h;
+    float wg[CW][EJ];
+#pragma unroll
+    for (int c = 0; c < CW; ++c)
+#pragma unroll
+        for (int j = 0; j < EJ; ++j) wg[c][j] = (kin && j0 + j < E) ? w_gate[(int64_t)(k0 + c) * E + j0 + j] : 0.f;
+    const int64_t t_begin = (int64_t)blockIdx.y * chunk_len;
+    const int64_t t_end = t_begin + chunk_len < T ? t_begin + chunk_len : T;
+    for (int64_t tb = t_begin; tb < t_end; tb += TT) {
+        __syncthreads();
+        for (int i = tid; i < TT * EJ; i += 256) {
+            const int tt = i / EJ, j = i - tt * EJ;
+            dl[tt][j] = (tb + tt < t_end && j0 + j < E) ? d_logits[(tb + tt) * E + j0 + j] : 0.f;
+        }
+        __syncthreads();
+        const int nt = (int)(t_end - tb < TT ? t_end - tb : TT);
+        if (!kin) continue;
+        for (int tt = 0; tt < nt; ++tt) {
+            bf16_t *row = d_x + (tb + tt) * h + k0;
+            float v[CW];
+            if (CW == 8) {
+                const bf16x8 b = *(const bf16x8 *)row;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) v[c] = (float)b[c];
+            } else {
+#pragma unroll
+                for (int c = 0; c < CW; ++c) v[c] = (float)row[c];
+            }
+#pragma unroll
+            for (int j = 0; j < EJ; ++j) {
+                const float g = dl[tt][j];
+#pragma unroll
+                for (int c = 0; c < CW; ++c) v[c] = fmaf(g, wg[c][j], v[c]);
+            }
+            if (CW == 8) {
+                bf16x8 b;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) b[c] = (bf16_t)v[c];
+                *(bf16x8 *)row = b;
+            } else {
+#pragma unroll
+                for (int c = 0; c < CW; ++c) row[c] = (bf16_t)v[c];
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ host side
+static int simple_chunks(const moe_shape_t *sh) {
+    int64_t n = (sh->T + 1023) / 1024;
+    return (int)(n < 1 ? 1 : (n > 32 ? 32 : n));
+}
+
+
+template <typename T>
+static void launch_gate_bwd_main(const moe_shape_t *sh, const void *x, const float *w_gate, const float *d_logits,
+                                 float *partial, void *d_x, int nch, int64_t chunk_len, hipStream_t s) {
+    dim3 grid((sh->h + 63) / 64, nch), block(256);
+    if (sh->E <= 16)
+        hipLaunchKernelGGL((gate_bwd_main_kernel<T, 16>), grid, block, 0, s, (const T *)x, w_gate, d_logits, partial,
+                           (T *)d_x, sh->T, sh->h, sh->E, chunk_len);
+    else if (sh->E <= 32)
+        hipLaunchKernelGGL((gate_bwd_main_kernel<T, 32>), grid, block, 0, s, (const T *)x, w_gate, d_logits, partial,
+                           (T *)d_x, sh->T, sh->h, sh->E, chunk_len);
+    else
+        hipLaunchKernelGGL((gate_bwd_main_kernel<T, 64>), grid, block, 0, s, (const T *)x, w_gate, d_logits, partial,
+                           (T *)d_x, sh->T, sh->h, sh->E, chunk_len);
+}
+
+static moe_status_t run_gate_bwd_simple(const moe_shape_t *sh, const float *d_gate_p, const float *probs, const int32_t *expert,
+                          const void *x, const float *w_gate, float *d_logits, float *d_w_gate, void *d_x_accum,
+                          void *ws, hipStream_t s) {
+    const int64_t n = sh->T * sh->E;
+    hipLaunchKernelGGL(gate_dlogits_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, d_gate_p, probs,
+                       expert, d_logits, sh->T, sh->E);
+    if (d_w_gate || d_x_accum) {
+        const int nch = simple_chunks(sh);
+        const int64_t chunk_len = (sh->T + nch - 1) / nch;
+        float *partial = d_w_gate ? (float *)ws : nullptr;
+        if (sh->dtype == MOE_BF16)
+            launch_gate_bwd_main<bf16_t>(sh, x, w_gate, d_logits, partial, d_x_accum, nch, chunk_len, s);
+        else
+            launch_gate_bwd_main<float>(sh, x, w_gate, d_logits, partial, d_x_accum, nch, chunk_len, s);
+        if (d_w_gate) {
+            const int64_t m = (int64_t)sh->h * sh->E;
+            hipLaunchKernelGGL(gate_dwg_reduce_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, s, partial,
+                               d_w_gate, m, nch);
+        }
+    }
+    return check_launch("gate_bwd");
+}
+
+
+// ---- workspace layout of the bf16 path: [planes 3*Epad*Tpad bf16][partial nchunks*Epad*h fp32]
+static int epad_of(int E) { return (E + 15) / 16 * 16; }
+static int64_t tpad_of(int64_t T) { return (T + 31) / 32 * 32; }
+static int dwg_chunks(const moe_shape_t *sh) {
+    int64_t n = (tpad_of(sh->T) + 511) / 512;
+    return (int)(n < 1 ? 1 : (n > 64 ? 64 : n));
+}
+static size_t planes_bytes(const moe_shape_t *sh) {
+    return (((size_t)3 * epad_of(sh->E) * tpad_of(sh->T) * 2) + 255) / 256 * 256;
+}
+
+size_t gate_bwd_ws_bytes(const moe_shape_t *sh) {
+    if (sh->dtype == MOE_BF16)
+        return planes_bytes(sh) + (size_t)dwg_chunks(sh) * epad_of(sh->E) * sh->h * 4;
+    return (size_t)simple_chunks(sh) * sh->h * sh->E * 4;
+}
+
+template <int CW, int EJ>
+static void launch_dx(const moe_shape_t *sh, const float *w_gate, const float *d_logits, void *d_x, int j0,
+                      hipStream_t s) {
+    const int64_t chunk_len = 256;
+    dim3 grid((unsigned)((sh->h + 256 * CW - 1) / (256 * CW)), (unsigned)((sh->T + chunk_len - 1) / chunk_len));
+    hipLaunchKernelGGL((gate_dx_kernel<CW, EJ>), grid, dim3(256), 0, s, w_gate, d_logits, (bf16_t *)d_x, sh->T, sh->h,
+                       sh->E, j0, chunk_len);
+}
+
+moe_status_t run_gate_bwd(const moe_shape_t *sh, const float *d_gate_p, const float *probs, const int32_t *expert,
+                          const void *x, const float *w_gate, float *d_logits, float *d_w_gate, void *d_x_accum,
+                          void *ws, hipStream_t s) {
+    if (sh->dtype != MOE_BF16)
+        return run_gate_bwd_simple(sh, d_gate_p, probs, expert, x, w_gate, d_logits, d_w_gate, d_x_accum, ws, s);
+    const int E = sh->E, Epad = epad_of(E);
+    const int64_t T = sh->T, Tpad = tpad_of(T);
+    if (!d_w_gate) {
+        const int64_t n = T * E;
+        hipLaunchKernelGGL(gate_dlogits_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, d_gate_p, probs,
+                           expert, d_logits, T, E);
+    } else {
+        bf16_t *planes = (bf16_t *)ws;
+        float *partial = (float *)((char *)ws + planes_bytes(sh));
+        const int64_t n = (int64_t)Epad * Tpad;
+        hipLaunchKernelGGL(gate_dlogits_planes_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, d_gate_p,
+                           probs, expert, d_logits, planes, T, E, Epad, Tpad);
+        const int nch = dwg_chunks(sh);
+        int64_t chunk_len = (Tpad + nch - 1) / nch;
+        chunk_len = (chunk_len + 31) / 32 * 32;
+        dim3 grid((unsigned)((sh->h + 255) / 256), (unsigned)nch);
+        const bf16_t *xb = (const bf16_t *)x;
+        // up to 64 experts per launch (4 accumulator blocks of 16 experts)
+        for (int e0 = 0; e0 < Epad; e0 += 64) {
+            const int nt16 = (Epad - e0 < 64 ? Epad - e0 : 64) / 16;
+            const bf16_t *pl = planes + (int64_t)e0 * Tpad;
+            float *pa = partial + (int64_t)e0 * sh->h;
+            switch (nt16) {
+                case 1: hipLaunchKernelGGL((gate_dwg_mfma_kernel<1>), grid, dim3(256), 0, s, xb, pl, pa, T, sh->h, Tpad, chunk_len, Epad); break;
+                case 2: hipLaunchKernelGGL((gate_dwg_mfma_kernel<2>), grid, dim3(256), 0, s, xb, pl, pa, T, sh->h, Tpad, chunk_len, Epad); break;
+                case 3: hipLaunchKernelGGL((gate_dwg_mfma_kernel<3>), grid, dim3(256), 0, s, xb, pl, pa, T, sh->h, Tpad, chunk_len, Epad); break;
+                default: hipLaunchKernelGGL((gate_dwg_mfma_kernel<4>), grid, dim3(256), 0, s, xb, pl, pa, T, sh->h, Tpad, chunk_len, Epad); break;
+            }
+        }
+        const int64_t m = (int64_t)E * sh->h;
+        hipLaunchKernelGGL(gate_dwg_reduce_t_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, s, partial,
+                           d_w_gate, sh->h, E, Epad, nch);
+    }
+    if (d_x_accum) {
+        if (E <= 16) launch_dx<8, 16>(sh, w_gate, d_logits, d_x_accum, 0, s);
+        else if (E <= 32) launch_dx<4, 32>(sh, w_gate, d_logits, d_x_accum, 0, s);
+        else
+            for (int j0 = 0; j0 < E; j0 += 64) launch_dx<2, 64>(sh, w_gate, d_logits, d_x_accum, j0, s);
+    }
+    return check_launch("gate_bwd");
+}
+
+}  // namespace moe

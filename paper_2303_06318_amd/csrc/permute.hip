@@ -1,4 +1,4 @@
-// HBM-streaming row movers: dispatch, combine and their backward, and the gate backward.
+// HBM-streaming row movers: dispatch, combine and their backward.
 // Every kernel moves whole rows with 16-byte accesses; one workgroup handles one row at a time.
 #include "moe_common.h"
 
@@ -133,75 +133,6 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const u32x4 *d_out, co
     }
 }
 
-// ------------------------------------------------------------------ gate backward
-// d_logits[t,j] = d_gate_p[t] * p_t * ([j == e_t] - probs[t,j])
-__global__ void gate_dlogits_kernel(const float *d_gate_p, const float *probs, const int32_t *expert, float *d_logits,
-                                    int64_t T, int E) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= T * E) return;
-    int64_t t = i / E;
-    int j = (int)(i - t * E);
-    int e = expert[t];
-    float pe = probs[t * E + e];
-    d_logits[i] = d_gate_p[t] * pe * ((j == e ? 1.f : 0.f) - probs[i]);
-}
-
-// Block = 64 columns of x (k0..k0+63) x 4 token lanes, token chunk [t0, t1).
-//   partial[chunk][k][j] = sum_{t in chunk} x[t,k] * d_logits[t,j]
-//   d_x[t,k] += sum_j d_logits[t,j] * w_gate[k,j]
-template <typename T, int EJ>
-__global__ __launch_bounds__(256) void gate_bwd_main_kernel(const T *x, const float *w_gate, const float *d_logits,
-                                                             float *partial, T *d_x, int64_t Tn, int h, int E,
-                                                             int64_t chunk_len) {
-    __shared__ float red[4][64][EJ + 1];
-    const int c = threadIdx.x & 63, tq = threadIdx.x >> 6;
-    const int k = blockIdx.x * 64 + c;
-    const bool kin = k < h;
-    const int64_t t0 = (int64_t)blockIdx.y * chunk_len;
-    const int64_t t1 = t0 + chunk_len < Tn ? t0 + chunk_len : Tn;
-    for (int j0 = 0; j0 < E; j0 += EJ) {
-        float wg[EJ], acc[EJ];
-#pragma unroll
-        for (int j = 0; j < EJ; ++j) {
-            wg[j] = (kin && j0 + j < E) ? w_gate[(int64_t)k * E + j0 + j] : 0.f;
-            acc[j] = 0.f;
-        }
-        for (int64_t t = t0 + tq; t < t1; t += 4) {
-            const float *dl = d_logits + t * E + j0;
-            const float xv = kin ? (float)x[t * h + k] : 0.f;
-            float dxa = 0.f;
-#pragma unroll
-            for (int j = 0; j < EJ; ++j) {
-                const float g = (j0 + j < E) ? dl[j] : 0.f;
-                acc[j] = fmaf(xv, g, acc[j]);
-                dxa = fmaf(g, wg[j], dxa);
-            }
-            if (d_x && kin) d_x[t * h + k] = (T)((float)d_x[t * h + k] + dxa);
-        }
-#pragma unroll
-        for (int j = 0; j < EJ; ++j) red[tq][c][j] = acc[j];
-        __syncthreads();
-        if (partial) {
-            for (int i = threadIdx.x; i < 64 * EJ; i += 256) {
-                int cc = i / EJ, j = i - cc * EJ;
-                int kk = blockIdx.x * 64 + cc;
-                if (kk < h && j0 + j < E)
-                    partial[((int64_t)blockIdx.y * h + kk) * E + j0 + j] =
-                        (red[0][cc][j] + red[1][cc][j]) + (red[2][cc][j] + red[3][cc][j]);
-            }
-        }
-        __syncthreads();
-    }
-}
-
-__global__ void gate_dwg_reduce_kernel(const float *partial, float *d_w_gate, int64_t n, int nchunks) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    float s = 0.f;
-    for (int c = 0; c < nchunks; ++c) s += partial[(int64_t)c * n + i];
-    d_w_gate[i] = s;
-}
-
 // ------------------------------------------------------------------ host side
 static unsigned row_grid(int64_t rows) { return (unsigned)(rows < 1048576 ? rows : 1048576); }
 
@@ -249,53 +180,6 @@ moe_status_t run_combine_bwd(const moe_shape_t *sh, const void *d_out, const voi
         hipLaunchKernelGGL(combine_bwd_kernel<float>, dim3(row_grid(rows)), dim3(256), 0, s, (const u32x4 *)d_out,
                            (const u32x4 *)y, token_of_slot, slot, gate_p, (u32x4 *)d_y, d_gate_p, rows, sh->T, words);
     return check_launch("combine_bwd");
-}
-
-int gate_bwd_chunks(const moe_shape_t *sh) {
-    int64_t n = (sh->T + 1023) / 1024;
-    return (int)(n < 1 ? 1 : (n > 32 ? 32 : n));
-}
-
-size_t gate_bwd_ws_bytes(const moe_shape_t *sh) {
-    return (size_t)gate_bwd_chunks(sh) * sh->h * sh->E * 4;
-}
-
-template <typename T>
-static void launch_gate_bwd_main(const moe_shape_t *sh, const void *x, const float *w_gate, const float *d_logits,
-                                 float *partial, void *d_x, int nch, int64_t chunk_len, hipStream_t s) {
-    dim3 grid((sh->h + 63) / 64, nch), block(256);
-    if (sh->E <= 16)
-        hipLaunchKernelGGL((gate_bwd_main_kernel<T, 16>), grid, block, 0, s, (const T *)x, w_gate, d_logits, partial,
-                           (T *)d_x, sh->T, sh->h, sh->E, chunk_len);
-    else if (sh->E <= 32)
-        hipLaunchKernelGGL((gate_bwd_main_kernel<T, 32>), grid, block, 0, s, (const T *)x, w_gate, d_logits, partial,
-                           (T *)d_x, sh->T, sh->h, sh->E, chunk_len);
-    else
-        hipLaunchKernelGGL((gate_bwd_main_kernel<T, 64>), grid, block, 0, s, (const T *)x, w_gate, d_logits, partial,
-                           (T *)d_x, sh->T, sh->h, sh->E, chunk_len);
-}
-
-moe_status_t run_gate_bwd(const moe_shape_t *sh, const float *d_gate_p, const float *probs, const int32_t *expert,
-                          const void *x, const float *w_gate, float *d_logits, float *d_w_gate, void *d_x_accum,
-                          void *ws, hipStream_t s) {
-    const int64_t n = sh->T * sh->E;
-    hipLaunchKernelGGL(gate_dlogits_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, d_gate_p, probs,
-                       expert, d_logits, sh->T, sh->E);
-    if (d_w_gate || d_x_accum) {
-        const int nch = gate_bwd_chunks(sh);
-        const int64_t chunk_len = (sh->T + nch - 1) / nch;
-        float *partial = d_w_gate ? (float *)ws : nullptr;
-        if (sh->dtype == MOE_BF16)
-            launch_gate_bwd_main<bf16_t>(sh, x, w_gate, d_logits, partial, d_x_accum, nch, chunk_len, s);
-        else
-            launch_gate_bwd_main<float>(sh, x, w_gate, d_logits, partial, d_x_accum, nch, chunk_len, s);
-        if (d_w_gate) {
-            const int64_t m = (int64_t)sh->h * sh->E;
-            hipLaunchKernelGGL(gate_dwg_reduce_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, s, partial,
-                               d_w_gate, m, nch);
-        }
-    }
-    return check_launch("gate_bwd");
 }
 
 }  // namespace moe

@@ -24,6 +24,8 @@ CASES = {
     "f32_bwd": synth.scaled(W["cfg1_tiny_f32"], T=700, h=72, f=100, E=5, capacity_factor=0.8, backward=True,
                             name="f32_bwd"),
     "bf16_one_expert": synth.scaled(W["cfg5_6p7b_tp4_fwdbwd"], T=600, h=264, f=328, E=1, capacity_factor=0.9),
+    "bf16_bwd_E64": synth.scaled(W["cfg4_skewed_fwd"], T=3000, h=264, f=136, E=64, backward=True),
+    "bf16_bwd_E200": synth.scaled(W["cfg5_6p7b_tp4_fwdbwd"], T=2100, h=136, f=72, E=200, capacity_factor=2.0),
 }
 
 
@@ -34,6 +36,10 @@ def run_forward(wl, act=moe.MOE_GELU_ERF, backward=None):
     layer.forward(dev.x, dev.wg, dev.w1, dev.w2, logit_bias=dev.bias)
     torch.cuda.synchronize()
     return inp, dev, layer
+
+
+def biased(inp, logits):
+    return logits if inp.logit_bias is None else (logits + inp.logit_bias[None, :]).astype(np.float32)
 
 
 def check_routing(orc, layer, wl, logits):
@@ -79,7 +85,7 @@ def test_forward_parity(orc, name):
     assert (out[slot < 0] == 0).all()
 
 
-@pytest.mark.parametrize("name", ["cfg5_small", "f32_bwd", "bf16_one_expert"])
+@pytest.mark.parametrize("name", ["cfg5_small", "f32_bwd", "bf16_one_expert", "bf16_bwd_E64", "bf16_bwd_E200"])
 @pytest.mark.parametrize("act", [moe.MOE_GELU_ERF, moe.MOE_GELU_TANH])
 def test_backward_parity(orc, name, act):
     wl = CASES[name]
