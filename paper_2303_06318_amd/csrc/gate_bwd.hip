@@ -239,6 +239,7 @@ __global__ __launch_bounds__(256) void gate_dx_kernel(const float *w_gate, const
         __syncthreads();
         const int nt = (int)(t_end - tb < TT ? t_end - tb : TT);
         if (!kin) continue;
+#pragma unroll 4
         for (int tt = 0; tt < nt; ++tt) {
             bf16_t *row = d_x + (tb + tt) * h + k0;
             float v[CW];
@@ -335,7 +336,7 @@ size_t gate_bwd_ws_bytes(const moe_shape_t *sh) {
 template <int CW, int EJ>
 static void launch_dx(const moe_shape_t *sh, const float *w_gate, const float *d_logits, void *d_x, int j0,
                       hipStream_t s) {
-    const int64_t chunk_len = 256;
+    const int64_t chunk_len = 64;
     dim3 grid((unsigned)((sh->h + 256 * CW - 1) / (256 * CW)), (unsigned)((sh->T + chunk_len - 1) / chunk_len));
     hipLaunchKernelGGL((gate_dx_kernel<CW, EJ>), grid, dim3(256), 0, s, w_gate, d_logits, (bf16_t *)d_x, sh->T, sh->h,
                        sh->E, j0, chunk_len);
