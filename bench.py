@@ -26,9 +26,10 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per GEMM launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/);
-# keyed by workload name.  None until measured.
-MEASURED_GEMM_TRAFFIC_BYTES = {}
+# HBM bytes per GEMM launch (average over the launches of a step) from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs, scaled by what the same counters read for a plain 1 GiB copy
+# (profiles/gemm_bf16_cfg5_fwdbwd.md, section 2); keyed by workload name, None where not measured.
+MEASURED_GEMM_TRAFFIC_BYTES = {"cfg5_6p7b_tp4_fwdbwd": 1.449e9}
 
 
 def main() -> int:
@@ -39,6 +40,8 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg5_6p7b_tp4_fwdbwd")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=768)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (known size) so that HBM counters can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU's share of the layer on ONE GPU; --gpus must be 1 "
@@ -99,6 +102,12 @@ def main() -> int:
                              layer.d_x, layer.ws)
             mark(8)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
