@@ -292,29 +292,58 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
     // 32-row blocks of this wave that hold valid rows (4 except in a last, partial m-tile)
     const int rv = Me - m0 - wm;
     const int nvi = __builtin_amdgcn_readfirstlane(rv >= 128 ? 4 : (rv <= 0 ? 0 : (rv + 31) >> 5));
-    auto rd = [&](bf16x8(&af)[4], bf16x8(&bf)[2], int stage, int ks, auto full) {
+    // Fragment reads and MFMAs in two halves per k-step, so that one iteration can be laid out as
+    // four pieces of {one global->LDS request, three fragment reads, four MFMAs}.
+    //   half 0 reads a[0], a[1], b[0], b[1] and multiplies rows 0-1; half 1 reads a[2], a[3], rows 2-3.
+    auto rd_half = [&](bf16x8(&af)[4], bf16x8(&bf)[2], int stage, int ks, int half, auto full) {
         if (DBG == 5 || DBG == 6) return;
         const char *ta = smem + stage * STAGE_BYTES, *tb = ta + OPER_BYTES;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (decltype(full)::value || i < nvi) af[i] = fa.read(ta, i, ks);
-        if (decltype(full)::value || nvi > 0) {
+        if (half == 0 && (decltype(full)::value || nvi > 0)) {
 #pragma unroll
             for (int j = 0; j < 2; ++j) bf[j] = fb.read(tb, j, ks);
         }
-    };
-    auto mma = [&](const bf16x8(&af)[4], const bf16x8(&bf)[2], auto full) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 2 * half; i < 2 * half + 2; ++i)
+            if (decltype(full)::value || i < nvi) af[i] = fa.read(ta, i, ks);
+    };
+    auto mma_half = [&](const bf16x8(&af)[4], const bf16x8(&bf)[2], int half, auto full) {
+#pragma unroll
+        for (int i = 2 * half; i < 2 * half + 2; ++i)
             if (decltype(full)::value || i < nvi) {
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], af[i], acc[i][j], 0, 0, 0);
             }
     };
+    // one of the four 1 KB chunk loads this wave contributes to a k-tile (2 per operand)
+    auto request_piece = [&](int kt, int stage, int piece) {
+        const int k0 = kt * BK;
+        const uint32_t base = smem_addr + stage * STAGE_BYTES;
+        if (piece < 2) {
+            const uint32_t kadd = AXC ? (uint32_t)k0 * d.lda * 2u : (uint32_t)k0 * 2u;
+            const uint32_t voff = k0 < la.kthr[piece] ? la.off[piece] + kadd : OOB;
+            load_to_lds(A, base + (uint32_t)(wave * 2 + piece) * 1024u, voff);
+        } else {
+            const int q = piece - 2;
+            const uint32_t kadd = BXC ? (uint32_t)k0 * d.ldb * 2u : (uint32_t)k0 * 2u;
+            const uint32_t voff = k0 < lb.kthr[q] ? lb.off[q] + kadd : OOB;
+            load_to_lds(B, base + OPER_BYTES + (uint32_t)(wave * 2 + q) * 1024u, voff);
+        }
+    };
+    auto interleave = [&]() {      // MFMA and LDS-read instructions alternate inside a piece
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+    };
+    auto mma = [&](const bf16x8(&af)[4], const bf16x8(&bf)[2], auto full) {
+        mma_half(af, bf, 0, full);
+        mma_half(af, bf, 1, full);
+    };
     auto request = [&](int kt, int stage) {
-        issue_loads<AXC>(A, la, d.lda, kt * BK, smem_addr + stage * STAGE_BYTES, wave);
-        issue_loads<BXC>(B, lb, d.ldb, kt * BK, smem_addr + stage * STAGE_BYTES + OPER_BYTES, wave);
+#pragma unroll
+        for (int piece = 0; piece < 4; ++piece) request_piece(kt, stage, piece);
     };
 #pragma unroll
     for (int i = 0; i < 4; ++i) a1[i] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
@@ -341,14 +370,28 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
             __builtin_amdgcn_s_waitcnt(0x0078);      // vmcnt(8) lgkmcnt(0)
             if (DBG != 6 && DBG != 7) __syncthreads();
             const int prev = stage == 0 ? NSTAGE - 1 : stage - 1;
-            if (DBG != 1 && DBG < 5) request(kt + NSTAGE - 1, prev);
-            rd(a0, b0, stage, 0, full);
+            const bool do_req = DBG != 1 && DBG < 5;
+            // piece 0..3: request one chunk of tile kt+3, read fragments, multiply (tile kt-1's
+            // second k-step first, then this tile's first k-step)
+            if (do_req) request_piece(kt + NSTAGE - 1, prev, 0);
+            rd_half(a0, b0, stage, 0, 0, full);
+            mma_half(a1, b1, 0, full);
+            interleave();
             __builtin_amdgcn_sched_barrier(0);
-            mma(a1, b1, full);                       // second k-step of tile kt-1
+            if (do_req) request_piece(kt + NSTAGE - 1, prev, 1);
+            rd_half(a0, b0, stage, 0, 1, full);
+            mma_half(a1, b1, 1, full);
+            interleave();
             __builtin_amdgcn_sched_barrier(0);
-            rd(a1, b1, stage, 1, full);
+            if (do_req) request_piece(kt + NSTAGE - 1, prev, 2);
+            rd_half(a1, b1, stage, 1, 0, full);
+            mma_half(a0, b0, 0, full);
+            interleave();
             __builtin_amdgcn_sched_barrier(0);
-            mma(a0, b0, full);
+            if (do_req) request_piece(kt + NSTAGE - 1, prev, 3);
+            rd_half(a1, b1, stage, 1, 1, full);
+            mma_half(a0, b0, 1, full);
+            interleave();
             __builtin_amdgcn_sched_barrier(0);
             stage = stage == NSTAGE - 1 ? 0 : stage + 1;
         }
