@@ -29,9 +29,21 @@
 namespace moe {
 
 constexpr int DBG = MOE_GEMM_DBG;
-constexpr int BM = 256, BN = 256, BK = 32, GEMM_THREADS = 512;
+#ifndef MOE_GEMM_BK
+#define MOE_GEMM_BK 32
+#endif
+constexpr int BM = 256, BN = 256, BK = MOE_GEMM_BK, GEMM_THREADS = 512;
+static_assert(BK == 32 || BK == 64, "k-tile depth");
+constexpr int KS = BK / 16;                    // MFMA k-steps per k-tile
+constexpr int CPW = BK / 16;                   // 1 KB chunks per wave, operand and k-tile
+constexpr int KC_ROW = BK * 2;                 // bytes of one KC row in LDS
+constexpr int KC_G = BK / 8;                   // 16-byte granules per KC row
+constexpr int KC_SWZ_SHIFT = BK == 32 ? 2 : 1; // rows per 256 bytes = 4 (BK 32) or 2 (BK 64)
 constexpr int LIGHT_ROWS = 128;                 // a last m-tile with at most this many rows is scheduled as "light"
-constexpr int NSTAGE = 4;                      // LDS stages; tiles are requested NSTAGE-1 k-tiles ahead
+#ifndef MOE_GEMM_NSTAGE
+#define MOE_GEMM_NSTAGE (MOE_GEMM_BK == 32 ? 4 : 2)
+#endif
+constexpr int NSTAGE = MOE_GEMM_NSTAGE;                      // LDS stages; tiles are requested NSTAGE-1 k-tiles ahead
 constexpr int OPER_BYTES = 256 * BK * 2;       // one operand's k-tile (16 KB)
 constexpr int STAGE_BYTES = 2 * OPER_BYTES;
 constexpr int CLD = BN + 8;                    // epilogue staging row (elements)
@@ -99,20 +111,20 @@ __device__ __forceinline__ void load_to_lds(const i32x4 &rsrc, uint32_t lds_addr
                  : "memory", "m0");
 }
 
-// Per-thread state of the global -> LDS copy of one operand.  A wave copies chunks 2*wave, 2*wave+1
-// of the tile's 16 one-KB chunks; lane L fills granule L of the chunk.
-//   KC chunk: 16 rows x 64 bytes, lane L -> row L/4, position L%4
+// Per-thread state of the global -> LDS copy of one operand.  A wave copies CPW consecutive chunks
+// of the tile's one-KB chunks; lane L fills granule L of the chunk.
+//   KC chunk: 1024 / KC_ROW rows, lane L -> row L / KC_G, position L % KC_G
 //   XC chunk: 2 k-rows x 512 bytes, lane L -> k-row L/32, position L%32
 struct Loader {
-    uint32_t off[2];    // byte offset of this lane's granule at k-tile 0 (OOB if outside the operand in x)
-    int32_t kthr[2];    // the granule is inside K for k-tile origin k0 iff k0 < kthr
+    uint32_t off[CPW];    // byte offset of this lane's granule at k-tile 0 (OOB if outside the operand in x)
+    int32_t kthr[CPW];    // the granule is inside K for k-tile origin k0 iff k0 < kthr
 };
 
 template <bool XC>
 __device__ __forceinline__ void loader_init(Loader &L, int ld, int x0, int xlim, int klim, int wave, int lane) {
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int chunk = wave * 2 + q;
+    for (int q = 0; q < CPW; ++q) {
+        const int chunk = wave * CPW + q;
         if (XC) {
             const int krow = chunk * 2 + (lane >> 5);
             const int g = (lane & 31) ^ ((krow & 3) << 2);
@@ -120,8 +132,8 @@ __device__ __forceinline__ void loader_init(Loader &L, int ld, int x0, int xlim,
             L.off[q] = gx < xlim ? ((uint32_t)krow * ld + gx) * 2u : OOB;
             L.kthr[q] = klim - krow;
         } else {
-            const int row = chunk * 16 + (lane >> 2);
-            const int g = (lane & 3) ^ ((row >> 2) & 3);
+            const int row = chunk * (1024 / KC_ROW) + lane / KC_G;
+            const int g = (lane % KC_G) ^ ((row >> KC_SWZ_SHIFT) & (KC_G - 1));
             const int gx = x0 + row;
             L.off[q] = gx < xlim ? ((uint32_t)gx * ld + g * 8) * 2u : OOB;
             L.kthr[q] = klim - g * 8;
@@ -129,27 +141,12 @@ __device__ __forceinline__ void loader_init(Loader &L, int ld, int x0, int xlim,
     }
 }
 
-template <bool XC>
-__device__ __forceinline__ void issue_loads(const i32x4 &rsrc, const Loader &L, int ld, int k0, uint32_t dst,
-                                            int wave) {
-    const uint32_t kadd = XC ? (uint32_t)k0 * ld * 2u : (uint32_t)k0 * 2u;
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const uint32_t voff = k0 < L.kthr[q] ? L.off[q] + kadd : OOB;
-        if (DBG == 9) {
-            u32x4 dummy;
-            asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(dummy) : "v"(voff), "s"(rsrc) : "memory");
-        } else
-        load_to_lds(rsrc, dst + (uint32_t)(wave * 2 + q) * 1024u, voff);
-    }
-}
-
 // Byte offsets (inside an operand tile) from which lane `lane` reads its MFMA fragments.
-//   KC: one offset per k-step (2), blocks of 32 rows add 32*64 bytes.
+//   KC: one offset per k-step, blocks of 32 rows add 32 * KC_ROW bytes.
 //   XC: one offset per 32-column block, k-steps add 16*512 bytes, the second half 4*512.
 template <bool XC, int NBLK>
 struct FragAddr {
-    int32_t a[XC ? NBLK : 2];
+    int32_t a[XC ? NBLK : KS];
     __device__ __forceinline__ void init(int xbase, int lane) {
         if (XC) {
             const int s = (lane >> 2) & 3;
@@ -159,10 +156,11 @@ struct FragAddr {
             for (int b = 0; b < NBLK; ++b)
                 a[b] = kr * 512 + (((((xbase + b * 32) >> 3) ^ (s << 2)) + glow) << 4) + (lane & 1) * 8;
         } else {
-            const int s = (lane >> 2) & 3;        // ((row >> 2) & 3) with row = xbase + lane%32, xbase % 32 == 0
+            // swizzle term of row = xbase + lane%32 (xbase is a multiple of 32, which the term ignores)
+            const int s = ((lane & 31) >> KC_SWZ_SHIFT) & (KC_G - 1);
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-                a[ks] = (xbase + (lane & 31)) * 64 + (((ks * 2 + (lane >> 5)) ^ s) << 4);
+            for (int ks = 0; ks < KS; ++ks)
+                a[ks] = (xbase + (lane & 31)) * KC_ROW + (((ks * 2 + (lane >> 5)) ^ s) << 4);
         }
     }
     __device__ __forceinline__ bf16x8 read(const char *tile, int blk, int ks) const {
@@ -174,7 +172,7 @@ struct FragAddr {
             s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             return __builtin_bit_cast(bf16x8, both);
         } else {
-            return *(const bf16x8 *)(tile + a[ks] + blk * 32 * 64);
+            return *(const bf16x8 *)(tile + a[ks] + blk * 32 * KC_ROW);
         }
     }
 };
@@ -315,19 +313,19 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[j], af[i], acc[i][j], 0, 0, 0);
             }
     };
-    // one of the four 1 KB chunk loads this wave contributes to a k-tile (2 per operand)
+    // one of the 2*CPW one-KB chunk loads this wave contributes to a k-tile (CPW per operand)
     auto request_piece = [&](int kt, int stage, int piece) {
         const int k0 = kt * BK;
         const uint32_t base = smem_addr + stage * STAGE_BYTES;
-        if (piece < 2) {
+        if (piece < CPW) {
             const uint32_t kadd = AXC ? (uint32_t)k0 * d.lda * 2u : (uint32_t)k0 * 2u;
             const uint32_t voff = k0 < la.kthr[piece] ? la.off[piece] + kadd : OOB;
-            load_to_lds(A, base + (uint32_t)(wave * 2 + piece) * 1024u, voff);
+            load_to_lds(A, base + (uint32_t)(wave * CPW + piece) * 1024u, voff);
         } else {
-            const int q = piece - 2;
+            const int q = piece - CPW;
             const uint32_t kadd = BXC ? (uint32_t)k0 * d.ldb * 2u : (uint32_t)k0 * 2u;
             const uint32_t voff = k0 < lb.kthr[q] ? lb.off[q] + kadd : OOB;
-            load_to_lds(B, base + OPER_BYTES + (uint32_t)(wave * 2 + q) * 1024u, voff);
+            load_to_lds(B, base + OPER_BYTES + (uint32_t)(wave * CPW + q) * 1024u, voff);
         }
     };
     auto interleave = [&]() {      // MFMA and LDS-read instructions alternate inside a piece
@@ -343,7 +341,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
     };
     auto request = [&](int kt, int stage) {
 #pragma unroll
-        for (int piece = 0; piece < 4; ++piece) request_piece(kt, stage, piece);
+        for (int piece = 0; piece < 2 * CPW; ++piece) request_piece(kt, stage, piece);
     };
 #pragma unroll
     for (int i = 0; i < 4; ++i) a1[i] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
@@ -366,33 +364,29 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
         for (int kt = 0; kt < nk; ++kt) {
             // tile kt has landed once at most the (NSTAGE-2) newer requests of 4 loads each are
             // outstanding; this wave's reads of tile kt-1 must be complete before its stage is reused
-            static_assert(NSTAGE == 4, "the wait count below is 4 * (NSTAGE - 2)");
-            __builtin_amdgcn_s_waitcnt(0x0078);      // vmcnt(8) lgkmcnt(0)
+            // (NSTAGE-2) newer tiles of 2*CPW loads each may still be in flight
+            constexpr int INFLIGHT = 2 * CPW * (NSTAGE - 2);
+            static_assert(INFLIGHT >= 0 && INFLIGHT < 16, "vmcnt immediate");
+            __builtin_amdgcn_s_waitcnt(0x0070 | INFLIGHT);      // vmcnt(INFLIGHT) lgkmcnt(0)
             if (DBG != 6 && DBG != 7) __syncthreads();
             const int prev = stage == 0 ? NSTAGE - 1 : stage - 1;
             const bool do_req = DBG != 1 && DBG < 5;
-            // piece 0..3: request one chunk of tile kt+3, read fragments, multiply (tile kt-1's
-            // second k-step first, then this tile's first k-step)
-            if (do_req) request_piece(kt + NSTAGE - 1, prev, 0);
-            rd_half(a0, b0, stage, 0, 0, full);
-            mma_half(a1, b1, 0, full);
-            interleave();
-            __builtin_amdgcn_sched_barrier(0);
-            if (do_req) request_piece(kt + NSTAGE - 1, prev, 1);
-            rd_half(a0, b0, stage, 0, 1, full);
-            mma_half(a1, b1, 1, full);
-            interleave();
-            __builtin_amdgcn_sched_barrier(0);
-            if (do_req) request_piece(kt + NSTAGE - 1, prev, 2);
-            rd_half(a1, b1, stage, 1, 0, full);
-            mma_half(a0, b0, 0, full);
-            interleave();
-            __builtin_amdgcn_sched_barrier(0);
-            if (do_req) request_piece(kt + NSTAGE - 1, prev, 3);
-            rd_half(a1, b1, stage, 1, 1, full);
-            mma_half(a0, b0, 1, full);
-            interleave();
-            __builtin_amdgcn_sched_barrier(0);
+            // 2*KS pieces: request one chunk of tile kt+NSTAGE-1, read half a k-step's fragments of
+            // this tile, multiply half of the previous k-step (tile kt-1's last one to begin with)
+#pragma unroll
+            for (int p = 0; p < 2 * KS; ++p) {
+                const int ks = p >> 1, half = p & 1;
+                if (do_req) request_piece(kt + NSTAGE - 1, prev, p);
+                if (ks & 1) {
+                    rd_half(a1, b1, stage, ks, half, full);
+                    mma_half(a0, b0, half, full);
+                } else {
+                    rd_half(a0, b0, stage, ks, half, full);
+                    mma_half(a1, b1, half, full);
+                }
+                interleave();
+                __builtin_amdgcn_sched_barrier(0);
+            }
             stage = stage == NSTAGE - 1 ? 0 : stage + 1;
         }
         mma(a1, b1, full);
