@@ -73,7 +73,7 @@ def main() -> int:
     sh = layer.shape
 
     phases = ["gate", "dispatch", "ffn_fwd", "combine"] + (
-        ["combine_bwd", "ffn_bwd", "dispatch_bwd", "gate_bwd"] if wl.backward else [])
+        ["combine_bwd", "gate_bwd", "ffn_bwd", "dispatch_bwd"] if wl.backward else [])
 
     def step(ev=None):
         def mark(i):
@@ -93,13 +93,13 @@ def main() -> int:
             moe.moe_combine_bwd(sh, d_out, layer.y, layer.token_of_slot, layer.slot, layer.gate_p, layer.d_y,
                                 layer.d_gate_p)
             mark(5)
+            moe.moe_gate_bwd(sh, layer.d_gate_p, layer.probs, layer.expert, x, wg, layer.d_logits, layer.d_w_gate,
+                             None, layer.ws)
+            mark(6)
             moe.moe_expert_ffn_bwd(sh, layer.d_y, layer.buf, layer.z_save, layer.hact, w1, w2, layer.kept,
                                    layer.d_buf, layer.d_w1, layer.d_w2, layer.ws)
-            mark(6)
-            moe.moe_dispatch_bwd(sh, layer.d_buf, layer.expert, layer.slot, layer.d_x)
             mark(7)
-            moe.moe_gate_bwd(sh, layer.d_gate_p, layer.probs, layer.expert, x, wg, layer.d_logits, layer.d_w_gate,
-                             layer.d_x, layer.ws)
+            moe.moe_dispatch_bwd(sh, layer.d_buf, layer.expert, layer.slot, layer.d_x, layer.d_logits, wg)
             mark(8)
 
     if args.copy_calibration:
@@ -151,8 +151,8 @@ def main() -> int:
     }
     if wl.backward:
         hbm["combine_bwd"] = 3 * n_kept * wl.h * esz
-        hbm["dispatch_bwd"] = n_kept * wl.h * esz + wl.T * wl.h * esz
-        hbm["gate_bwd"] = wl.T * wl.h * esz * 3 + wl.T * wl.E * 4 * 2
+        hbm["dispatch_bwd"] = n_kept * wl.h * esz + wl.T * wl.h * esz      # gate's d_x term fused in
+        hbm["gate_bwd"] = wl.T * wl.h * esz + wl.T * wl.E * 4 * 2           # d_logits, d_w_gate (reads x once)
     hbm_frac = {p: round(b / (phase_ms[p] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) for p, b in hbm.items()}
 
     cpu_baseline = None

@@ -162,15 +162,22 @@ moe_status_t moe_expert_ffn_bwd(const moe_shape_t *shape, const void *d_y, const
 
 /*
  * Dispatch backward:  d_x[t,:] = d_buf[expert[t], slot[t], :] if slot[t] >= 0 else 0.
- *   d_buf [E,C,h], expert [T], slot [T], d_x [T,h].
+ * If d_logits and w_gate are given (both or neither), the gate's contribution to the token gradient
+ * is added in the same pass:  d_x[t,:] += d_logits[t,:] w_gate^T  (d_logits from moe_gate_bwd), so
+ * d_x is written once.
+ *   d_buf [E,C,h], expert [T], slot [T], d_x [T,h] (out), d_logits [T,E] f32 or NULL,
+ *   w_gate [h,E] f32 or NULL.
  */
 moe_status_t moe_dispatch_bwd(const moe_shape_t *shape, const void *d_buf, const int32_t *expert,
-                              const int32_t *slot, void *d_x, void *stream);
+                              const int32_t *slot, void *d_x, const float *d_logits, const float *w_gate,
+                              void *stream);
 
 /*
  * Gate backward (the gate only receives gradient through p_t).
  *   d_logits[t,j] = d_gate_p[t] * p_t * ([j == e_t] - probs[t,j])
- *   d_w_gate = x^T d_logits ;  d_x_accum[t,:] += d_logits[t,:] w_gate^T   (if d_x_accum != NULL)
+ *   d_w_gate = x^T d_logits ;  d_x_accum[t,:] += d_logits[t,:] w_gate^T   (if d_x_accum != NULL; the
+ *   same term can instead be fused into moe_dispatch_bwd, which is the cheaper order:
+ *   moe_combine_bwd, moe_gate_bwd(d_x_accum = NULL), moe_expert_ffn_bwd, moe_dispatch_bwd(d_logits, w_gate))
  *   d_gate_p [T] f32, probs [T,E] f32, expert [T], x [T,h], w_gate [h,E] f32,
  *   d_logits [T,E] f32 (out), d_w_gate [h,E] f32 (out, overwritten) or NULL,
  *   d_x_accum [T,h] dtype (in/out) or NULL.

@@ -213,11 +213,15 @@ __global__ void gate_dwg_reduce_t_kernel(const float *partial, float *d_w_gate, 
     d_w_gate[(int64_t)k * E + j] = s;
 }
 
-// d_x[t, k] += sum_j dL[t,j] * w_gate[k,j].  A thread keeps CW columns x EJ experts of w_gate in
+// d_x[t, k] (+)= sum_j dL[t,j] * w_gate[k,j].  A thread keeps CW columns x EJ experts of w_gate in
 // registers and walks the tokens of its chunk; dL rows are broadcast from LDS.
+// With d_buf == nullptr the sum is added to d_x in place.  With d_buf given, the dispatch backward
+// is fused in: d_x[t,:] = d_buf[expert[t], slot[t], :] (0 for a dropped token) + the sum, so d_x is
+// written once instead of written, read and written again.
 template <int CW, int EJ>
 __global__ __launch_bounds__(256) void gate_dx_kernel(const float *w_gate, const float *d_logits, bf16_t *d_x, int64_t T,
-                                                       int h, int E, int j0, int64_t chunk_len) {
+                                                       int h, int E, int j0, int64_t chunk_len, const bf16_t *d_buf,
+                                                       const int32_t *expert, const int32_t *slot, int64_t C) {
     constexpr int TT = 64;
     __shared__ float dl[TT][EJ];
     const int tid = threadIdx.x;
@@ -239,32 +243,54 @@ __global__ __launch_bounds__(256) void gate_dx_kernel(const float *w_gate, const
         __syncthreads();
         const int nt = (int)(t_end - tb < TT ? t_end - tb : TT);
         if (!kin) continue;
-#pragma unroll 4
-        for (int tt = 0; tt < nt; ++tt) {
-            bf16_t *row = d_x + (tb + tt) * h + k0;
-            float v[CW];
-            if (CW == 8) {
-                const bf16x8 b = *(const bf16x8 *)row;
+        // groups of 4 tokens: issue the 4 row loads, then the arithmetic, then the 4 stores
+        for (int t4 = 0; t4 < nt; t4 += 4) {
+            float v[4][CW];
 #pragma unroll
-                for (int c = 0; c < 8; ++c) v[c] = (float)b[c];
-            } else {
+            for (int u = 0; u < 4; ++u) {
+                const int tt = t4 + u;
+                bool zero = tt >= nt;
+                const bf16_t *src = d_x + (tb + (zero ? 0 : tt)) * h + k0;
+                if (d_buf && !zero) {
+                    const int sl = slot[tb + tt];
+                    zero = sl < 0;
+                    src = d_buf + ((int64_t)expert[tb + tt] * C + (zero ? 0 : sl)) * h + k0;
+                }
+                if (zero) {
 #pragma unroll
-                for (int c = 0; c < CW; ++c) v[c] = (float)row[c];
+                    for (int c = 0; c < CW; ++c) v[u][c] = 0.f;
+                } else if (CW == 8) {
+                    const bf16x8 b = *(const bf16x8 *)src;
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) v[u][c] = (float)b[c];
+                } else {
+#pragma unroll
+                    for (int c = 0; c < CW; ++c) v[u][c] = (float)src[c];
+                }
             }
 #pragma unroll
             for (int j = 0; j < EJ; ++j) {
-                const float g = dl[tt][j];
 #pragma unroll
-                for (int c = 0; c < CW; ++c) v[c] = fmaf(g, wg[c][j], v[c]);
+                for (int u = 0; u < 4; ++u) {
+                    const float g = dl[(t4 + u) & (TT - 1)][j];
+#pragma unroll
+                    for (int c = 0; c < CW; ++c) v[u][c] = fmaf(g, wg[c][j], v[u][c]);
+                }
             }
-            if (CW == 8) {
-                bf16x8 b;
 #pragma unroll
-                for (int c = 0; c < 8; ++c) b[c] = (bf16_t)v[c];
-                *(bf16x8 *)row = b;
-            } else {
+            for (int u = 0; u < 4; ++u) {
+                const int tt = t4 + u;
+                if (tt >= nt) continue;
+                bf16_t *row = d_x + (tb + tt) * h + k0;
+                if (CW == 8) {
+                    bf16x8 b;
 #pragma unroll
-                for (int c = 0; c < CW; ++c) row[c] = (bf16_t)v[c];
+                    for (int c = 0; c < 8; ++c) b[c] = (bf16_t)v[u][c];
+                    *(bf16x8 *)row = b;
+                } else {
+#pragma unroll
+                    for (int c = 0; c < CW; ++c) row[c] = (bf16_t)v[u][c];
+                }
             }
         }
     }
@@ -335,11 +361,12 @@ size_t gate_bwd_ws_bytes(const moe_shape_t *sh) {
 
 template <int CW, int EJ>
 static void launch_dx(const moe_shape_t *sh, const float *w_gate, const float *d_logits, void *d_x, int j0,
-                      hipStream_t s) {
+                      hipStream_t s, const void *d_buf = nullptr, const int32_t *expert = nullptr,
+                      const int32_t *slot = nullptr) {
     const int64_t chunk_len = 64;
     dim3 grid((unsigned)((sh->h + 256 * CW - 1) / (256 * CW)), (unsigned)((sh->T + chunk_len - 1) / chunk_len));
     hipLaunchKernelGGL((gate_dx_kernel<CW, EJ>), grid, dim3(256), 0, s, w_gate, d_logits, (bf16_t *)d_x, sh->T, sh->h,
-                       sh->E, j0, chunk_len);
+                       sh->E, j0, chunk_len, (const bf16_t *)d_buf, expert, slot, sh->C);
 }
 
 moe_status_t run_gate_bwd(const moe_shape_t *sh, const float *d_gate_p, const float *probs, const int32_t *expert,
@@ -387,6 +414,40 @@ moe_status_t run_gate_bwd(const moe_shape_t *sh, const float *d_gate_p, const fl
             for (int j0 = 0; j0 < E; j0 += 64) launch_dx<2, 64>(sh, w_gate, d_logits, d_x_accum, j0, s);
     }
     return check_launch("gate_bwd");
+}
+
+// fp32 storage: d_x[t,k] += sum_j d_logits[t,j] * w_gate[k,j], one thread per element (small workloads only)
+__global__ void gate_dx_f32_kernel(const float *w_gate, const float *d_logits, float *d_x, int64_t T, int h, int E) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= T * h) return;
+    const int64_t t = i / h;
+    const int k = (int)(i - t * h);
+    float s = 0.f;
+    for (int j = 0; j < E; ++j) s = fmaf(d_logits[t * E + j], w_gate[(int64_t)k * E + j], s);
+    d_x[i] += s;
+}
+
+moe_status_t run_gate_dx_f32(const moe_shape_t *sh, const float *d_logits, const float *w_gate, void *d_x,
+                             hipStream_t s) {
+    const int64_t n = sh->T * sh->h;
+    hipLaunchKernelGGL(gate_dx_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, w_gate, d_logits,
+                       (float *)d_x, sh->T, sh->h, sh->E);
+    return check_launch("gate_dx_f32");
+}
+
+// Dispatch backward with the gate's contribution fused in (bf16 storage):
+//   d_x[t,:] = d_buf[expert[t], slot[t], :] (or 0) + d_logits[t,:] w_gate^T
+moe_status_t run_dispatch_bwd_fused(const moe_shape_t *sh, const void *d_buf, const int32_t *expert,
+                                    const int32_t *slot, void *d_x, const float *d_logits, const float *w_gate,
+                                    hipStream_t s) {
+    const int E = sh->E;
+    if (E <= 16) launch_dx<8, 16>(sh, w_gate, d_logits, d_x, 0, s, d_buf, expert, slot);
+    else if (E <= 32) launch_dx<4, 32>(sh, w_gate, d_logits, d_x, 0, s, d_buf, expert, slot);
+    else {
+        launch_dx<2, 64>(sh, w_gate, d_logits, d_x, 0, s, d_buf, expert, slot);
+        for (int j0 = 64; j0 < E; j0 += 64) launch_dx<2, 64>(sh, w_gate, d_logits, d_x, j0, s);
+    }
+    return check_launch("dispatch_bwd_fused");
 }
 
 }  // namespace moe

@@ -38,6 +38,9 @@ moe_status_t run_combine_bwd(const moe_shape_t *, const void *, const void *, co
                              const float *, void *, float *, hipStream_t);
 moe_status_t run_gate_bwd(const moe_shape_t *, const float *, const float *, const int32_t *, const void *,
                           const float *, float *, float *, void *, void *, hipStream_t);
+moe_status_t run_dispatch_bwd_fused(const moe_shape_t *, const void *, const int32_t *, const int32_t *, void *,
+                                    const float *, const float *, hipStream_t);
+moe_status_t run_gate_dx_f32(const moe_shape_t *, const float *, const float *, void *, hipStream_t);
 
 static size_t esize(const moe_shape_t *sh) { return sh->dtype == MOE_BF16 ? 2 : 4; }
 
@@ -299,14 +302,26 @@ moe_status_t moe_expert_ffn_bwd(const moe_shape_t *shape, const void *d_y, const
 }
 
 moe_status_t moe_dispatch_bwd(const moe_shape_t *shape, const void *d_buf, const int32_t *expert, const int32_t *slot,
-                              void *d_x, void *stream) {
+                              void *d_x, const float *d_logits, const float *w_gate, void *stream) {
     moe_status_t st = check_shape(shape);
     if (st != MOE_OK) return st;
     REQUIRE_PTR(d_buf);
     REQUIRE_PTR(expert);
     REQUIRE_PTR(slot);
     REQUIRE_PTR(d_x);
-    return run_dispatch_bwd(shape, d_buf, expert, slot, d_x, (hipStream_t)stream);
+    OPTIONAL_PTR(d_logits);
+    OPTIONAL_PTR(w_gate);
+    if ((d_logits == nullptr) != (w_gate == nullptr)) {
+        set_error("moe_dispatch_bwd: d_logits and w_gate must be given together");
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (d_logits == nullptr) return run_dispatch_bwd(shape, d_buf, expert, slot, d_x, (hipStream_t)stream);
+    if (shape->dtype == MOE_BF16)
+        return run_dispatch_bwd_fused(shape, d_buf, expert, slot, d_x, d_logits, w_gate, (hipStream_t)stream);
+    // fp32 storage: plain row gather, then the gate part added in place
+    st = run_dispatch_bwd(shape, d_buf, expert, slot, d_x, (hipStream_t)stream);
+    if (st != MOE_OK) return st;
+    return run_gate_dx_f32(shape, d_logits, w_gate, d_x, (hipStream_t)stream);
 }
 
 moe_status_t moe_gate_bwd(const moe_shape_t *shape, const float *d_gate_p, const float *probs, const int32_t *expert,

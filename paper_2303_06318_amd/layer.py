@@ -65,13 +65,20 @@ class MoeLayer:
         moe.moe_combine(self.shape, self.y, self.expert, self.slot, self.gate_p, self.out)
         return self.out
 
-    def backward(self, d_out, x, w_gate, w1, w2):
+    def backward(self, d_out, x, w_gate, w1, w2, fused=True):
         assert self.backward_enabled
         moe.moe_combine_bwd(self.shape, d_out, self.y, self.token_of_slot, self.slot, self.gate_p, self.d_y,
                             self.d_gate_p)
+        if fused:
+            # gate backward first (it only needs d_gate_p), so that the token gradient is written once
+            moe.moe_gate_bwd(self.shape, self.d_gate_p, self.probs, self.expert, x, w_gate, self.d_logits,
+                             self.d_w_gate, None, self.ws)
         moe.moe_expert_ffn_bwd(self.shape, self.d_y, self.buf, self.z_save, self.hact, w1, w2, self.kept, self.d_buf,
                                self.d_w1, self.d_w2, self.ws)
-        moe.moe_dispatch_bwd(self.shape, self.d_buf, self.expert, self.slot, self.d_x)
-        moe.moe_gate_bwd(self.shape, self.d_gate_p, self.probs, self.expert, x, w_gate, self.d_logits, self.d_w_gate,
-                         self.d_x, self.ws)
+        if fused:
+            moe.moe_dispatch_bwd(self.shape, self.d_buf, self.expert, self.slot, self.d_x, self.d_logits, w_gate)
+        else:
+            moe.moe_dispatch_bwd(self.shape, self.d_buf, self.expert, self.slot, self.d_x)
+            moe.moe_gate_bwd(self.shape, self.d_gate_p, self.probs, self.expert, x, w_gate, self.d_logits,
+                             self.d_w_gate, self.d_x, self.ws)
         return self.d_x, self.d_w1, self.d_w2, self.d_w_gate

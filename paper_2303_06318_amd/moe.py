@@ -60,7 +60,7 @@ def lib():
             "moe_combine": [sp] + [vp] * 5 + [vp],
             "moe_combine_bwd": [sp] + [vp] * 7 + [vp],
             "moe_expert_ffn_bwd": [sp] + [vp] * 10 + [vp, sz, vp],
-            "moe_dispatch_bwd": [sp] + [vp] * 4 + [vp],
+            "moe_dispatch_bwd": [sp] + [vp] * 6 + [vp],
             "moe_gate_bwd": [sp] + [vp] * 8 + [vp, sz, vp],
         }
         for name, args in sig.items():
@@ -147,8 +147,9 @@ def moe_expert_ffn_bwd(shape, d_y, buf, z_save, hact, w1, w2, kept, d_buf, d_w1,
                                     _stream(stream)))
 
 
-def moe_dispatch_bwd(shape, d_buf, expert, slot, d_x, stream=None):
-    _check(lib().moe_dispatch_bwd(C.byref(shape), _ptr(d_buf), _ptr(expert), _ptr(slot), _ptr(d_x), _stream(stream)))
+def moe_dispatch_bwd(shape, d_buf, expert, slot, d_x, d_logits=None, w_gate=None, stream=None):
+    _check(lib().moe_dispatch_bwd(C.byref(shape), _ptr(d_buf), _ptr(expert), _ptr(slot), _ptr(d_x), _ptr(d_logits),
+                                  _ptr(w_gate), _stream(stream)))
 
 
 def moe_gate_bwd(shape, d_gate_p, probs, expert, x, w_gate, d_logits, d_w_gate, d_x_accum, ws, stream=None):

@@ -209,3 +209,20 @@ def test_dispatch_combine_round_trip_bitwise(orc):
     assert (slot < 0).any()
     assert np.array_equal(out[slot >= 0], inp.x[slot >= 0])
     assert (out[slot < 0] == 0).all()
+
+
+@pytest.mark.parametrize("name", ["cfg5_small", "f32_bwd", "bf16_bwd_E200"])
+def test_backward_unfused_order(orc, name):
+    """The two-call order (dispatch backward, then gate backward accumulating into d_x) gives the same
+    gradients as the fused order the layer uses by default."""
+    wl = CASES[name]
+    inp, dev, layer = run_forward(wl, backward=True)
+    layer.backward(dev.d_out, dev.x, dev.wg, dev.w1, dev.w2, fused=False)
+    torch.cuda.synchronize()
+    g_logits = host(layer.logits)
+    fw = orc.layer_forward(inp.x, inp.wg, inp.w1, inp.w2, wl.C, logits=g_logits)
+    bw = orc.layer_backward(fw, inp.d_out, inp.x, inp.wg, inp.w1, inp.w2)
+    t = tol(wl)
+    assert relfro(host(layer.d_x), bw["dX"]) <= t
+    assert relfro(host(layer.d_w_gate), bw["dWg"]) <= t
+    assert relfro(host(layer.d_logits), bw["dL"]) <= t
