@@ -224,6 +224,7 @@ __global__ __launch_bounds__(256) void gate_dx_kernel(const float *w_gate, const
                                                        const int32_t *expert, const int32_t *slot, int64_t C) {
     constexpr int TT = 64;
     __shared__ float dl[TT][EJ];
+    __shared__ int32_t srow[TT];      // fused gather: buffer row of each token, -1 if dropped
     const int tid = threadIdx.x;
     const int k0 = (blockIdx.x * 256 + tid) * CW;
     const bool kin = k0 < h;
@@ -240,6 +241,10 @@ __global__ __launch_bounds__(256) void gate_dx_kernel(const float *w_gate, const
             const int tt = i / EJ, j = i - tt * EJ;
             dl[tt][j] = (tb + tt < t_end && j0 + j < E) ? d_logits[(tb + tt) * E + j0 + j] : 0.f;
         }
+        if (d_buf && tid < TT && tb + tid < t_end) {
+            const int sl = slot[tb + tid];
+            srow[tid] = sl < 0 ? -1 : (int32_t)((int64_t)expert[tb + tid] * C + sl);
+        }
         __syncthreads();
         const int nt = (int)(t_end - tb < TT ? t_end - tb : TT);
         if (!kin) continue;
@@ -252,9 +257,9 @@ __global__ __launch_bounds__(256) void gate_dx_kernel(const float *w_gate, const
                 bool zero = tt >= nt;
                 const bf16_t *src = d_x + (tb + (zero ? 0 : tt)) * h + k0;
                 if (d_buf && !zero) {
-                    const int sl = slot[tb + tt];
-                    zero = sl < 0;
-                    src = d_buf + ((int64_t)expert[tb + tt] * C + (zero ? 0 : sl)) * h + k0;
+                    const int r = srow[tt];
+                    zero = r < 0;
+                    src = d_buf + (int64_t)(zero ? 0 : r) * h + k0;
                 }
                 if (zero) {
 #pragma unroll
