@@ -72,29 +72,45 @@ __global__ __launch_bounds__(256) void gate_bf16_kernel(const bf16_t *x, const b
 #pragma unroll
         for (int n = 0; n < NT; ++n) acc[r][n] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    // Buffer resources: rows beyond the last token and k beyond h read as zero, so the loop has no
+    // branches and U k-steps of loads are in flight per wave before their MFMAs issue.
+    constexpr int U = 4;
+    constexpr uint32_t OOB = 0x80000000u;
+    const int64_t rows = T - t0 < TM ? T - t0 : TM;
+    const __amdgpu_buffer_rsrc_t xr =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(x + t0 * h), 0, (int)(rows * h * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t pr =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(planes), 0, (int)(3 * plane * 2), 0x00020000);
     const int nsteps = (h + 31) / 32;
-    for (int s = wave; s < nsteps; s += 4) {
-        const int k = s * 32 + g * 8;
-        const bool kin = k < h;
-        bf16x8 a[R];
+    for (int s = wave; s < nsteps; s += 4 * U) {
+        bf16x8 a[U][R];
+        uint32_t koff[U];
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            int64_t t = t0 + r * 16 + i16;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (kin && t < T) v = __builtin_nontemporal_load((const u32x4 *)(x + t * h + k));
-            a[r] = __builtin_bit_cast(bf16x8, v);
+        for (int u = 0; u < U; ++u) {
+            const int k = (s + 4 * u) * 32 + g * 8;
+            koff[u] = k < h ? (uint32_t)k * 2u : OOB;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                a[u][r] = __builtin_bit_cast(
+                    bf16x8, __builtin_amdgcn_raw_buffer_load_b128(xr, (uint32_t)(r * 16 + i16) * h * 2u + koff[u], 0, 0));
         }
 #pragma unroll
         for (int n = 0; n < NT; ++n) {
+            bf16x8 b[U][3];
 #pragma unroll
-            for (int p = 0; p < 3; ++p) {
-                u32x4 v = {0u, 0u, 0u, 0u};
-                if (kin) v = *(const u32x4 *)(planes + p * plane + (int64_t)(n * 16 + i16) * h + k);
-                bf16x8 b = __builtin_bit_cast(bf16x8, v);
+            for (int u = 0; u < U; ++u)
 #pragma unroll
-                for (int r = 0; r < R; ++r)
-                    acc[r][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[r], b, acc[r][n], 0, 0, 0);
-            }
+                for (int p = 0; p < 3; ++p)
+                    b[u][p] = __builtin_bit_cast(
+                        bf16x8, __builtin_amdgcn_raw_buffer_load_b128(
+                                    pr, (uint32_t)(p * plane + (int64_t)(n * 16 + i16) * h) * 2u + koff[u], 0, 0));
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int p = 0; p < 3; ++p)
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+                        acc[r][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][r], b[u][p], acc[r][n], 0, 0, 0);
         }
     }
     // 16x16 result: lane holds column (expert) lane%16, rows (tokens) 4*(lane/16) + v
