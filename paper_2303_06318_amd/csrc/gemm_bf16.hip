@@ -3,10 +3,11 @@
 // fused GeLU', dD = dZ W1^T) and weight gradients (dW = A^T B over the kept rows).
 //
 // One workgroup of 512 threads (8 waves, 2 x 4) owns a 256 x 256 output tile of one expert and
-// walks K in steps of 64 through two 64 KB LDS stages.  Each wave owns 128 x 64 of the tile:
-// 4 x 2 MFMA blocks of 32 x 32.  Global data goes straight into LDS (buffer_load ... lds, 16
-// bytes per lane, no register staging); out-of-range lanes deliver zeros, so ragged row counts
-// and K tails need no branches.
+// walks K in 32-deep tiles through four 32 KB LDS stages (three tiles, 96 KB, in flight).  Each
+// wave owns 128 x 64 of the tile: 4 x 2 MFMA blocks of 32 x 32.  Global data goes straight into
+// LDS (buffer_load ... lds, 16 bytes per lane, no register staging); out-of-range lanes deliver
+// zeros, so ragged row counts and K tails need no branches.  The two waves of a SIMD alternate
+// between a memory phase and an MFMA phase, half an iteration apart (see the main loop).
 //
 // Operands are taken in the layout the layer stores them in, so no transposed copy is ever made:
 //   "KC" operand: the reduction index is contiguous in memory  -> LDS tile [256 x][64 k], 16-byte
@@ -22,13 +23,22 @@
 #include <type_traits>
 #include "moe_common.h"
 
+// Timing experiments only; every non-zero variant computes wrong results and is never built into
+// the library.  1: no global->LDS loads; 5: no LDS fragment reads; 6: neither (MFMA and barriers
+// only); 7: every k-tile re-reads k-tile 0 (loads hit the vector L1); 8: k wraps after 8 tiles
+// (loads hit L2).  MOE_GEMM_TL: each workgroup writes {wall start, wall end, shader cycles, tile id}
+// to d.C2 (4 x int64 per workgroup) for a timeline of the launch.
 #ifndef MOE_GEMM_DBG
-#define MOE_GEMM_DBG 0     // timing experiments only (non-zero variants compute wrong results)
+#define MOE_GEMM_DBG 0
 #endif
 
 namespace moe {
 
 constexpr int DBG = MOE_GEMM_DBG;
+#ifndef MOE_GEMM_TL
+#define MOE_GEMM_TL 0
+#endif
+constexpr bool TL = MOE_GEMM_TL != 0;
 #ifndef MOE_GEMM_BK
 #define MOE_GEMM_BK 32
 #endif
@@ -186,6 +196,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
     // share an L2) and, after those, the x-th eighth of the light list: the cheap tiles fill the
     // last, partial round of the grid instead of idling compute units.  kept[] lives on the
     // device, so every workgroup derives the lists itself with a short scalar scan over experts.
+    const long long t_entry = TL ? clock64() : 0;
+    const long long w_entry = TL ? wall_clock64() : 0;
     const int pid = blockIdx.x;
     const int xcd = pid & 7, local = pid >> 3;
     const int lane_s = threadIdx.x & 63;
@@ -276,9 +288,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
     const int nk = (Ke + BK - 1) / BK;
     // Software pipeline.  A k-tile is 32 deep: 2 k-steps of 8 MFMAs per wave.  Tile kt lives in
     // stage kt % NSTAGE and is requested NSTAGE-1 iterations before it is consumed, so up to
-    // (NSTAGE-1) x 32 KB are in flight per workgroup; that, not the MFMA rate, is what bounds this
-    // kernel when HBM latency is exposed.  Fragments alternate between two register sets so that
-    // every LDS read is issued one k-step (8 MFMAs) before its use.
+    // (NSTAGE-1) x 32 KB are in flight per workgroup.  Each k-step has its own fragment registers
+    // (a0/b0, a1/b1), all read in the memory phase that precedes the tile's 16 MFMAs.
     bf16x8 a0[4], b0[2], a1[4], b1[2];
     Loader la, lb;
     loader_init<AXC>(la, d.lda, m0, Me, Ke, wave, lane);
@@ -290,11 +301,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
     // 32-row blocks of this wave that hold valid rows (4 except in a last, partial m-tile)
     const int rv = Me - m0 - wm;
     const int nvi = __builtin_amdgcn_readfirstlane(rv >= 128 ? 4 : (rv <= 0 ? 0 : (rv + 31) >> 5));
-    // Fragment reads and MFMAs in two halves per k-step, so that one iteration can be laid out as
-    // four pieces of {one global->LDS request, three fragment reads, four MFMAs}.
-    //   half 0 reads a[0], a[1], b[0], b[1] and multiplies rows 0-1; half 1 reads a[2], a[3], rows 2-3.
+    // Fragment reads and MFMAs of one k-step, in halves: half 0 covers a[0], a[1], b[0], b[1] and
+    // block rows 0-1, half 1 a[2], a[3] and block rows 2-3.  In a partial m-tile (full = false)
+    // blocks without valid rows are skipped.
+    bool rd_enable = true;
     auto rd_half = [&](bf16x8(&af)[4], bf16x8(&bf)[2], int stage, int ks, int half, auto full) {
-        if (DBG == 5 || DBG == 6) return;
+        if ((DBG == 5 || DBG == 6) && !rd_enable) return;
         const char *ta = smem + stage * STAGE_BYTES, *tb = ta + OPER_BYTES;
         if (half == 0 && (decltype(full)::value || nvi > 0)) {
 #pragma unroll
@@ -315,7 +327,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
     };
     // one of the 2*CPW one-KB chunk loads this wave contributes to a k-tile (CPW per operand)
     auto request_piece = [&](int kt, int stage, int piece) {
-        const int k0 = kt * BK;
+        const int k0 = (DBG == 7 ? 0 : DBG == 8 ? (kt & 7) : kt) * BK;
         const uint32_t base = smem_addr + stage * STAGE_BYTES;
         if (piece < CPW) {
             const uint32_t kadd = AXC ? (uint32_t)k0 * d.lda * 2u : (uint32_t)k0 * 2u;
@@ -326,13 +338,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
             const uint32_t kadd = BXC ? (uint32_t)k0 * d.ldb * 2u : (uint32_t)k0 * 2u;
             const uint32_t voff = k0 < lb.kthr[q] ? lb.off[q] + kadd : OOB;
             load_to_lds(B, base + OPER_BYTES + (uint32_t)(wave * CPW + q) * 1024u, voff);
-        }
-    };
-    auto interleave = [&]() {      // MFMA and LDS-read instructions alternate inside a piece
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
     };
     auto mma = [&](const bf16x8(&af)[4], const bf16x8(&bf)[2], auto full) {
@@ -354,42 +359,60 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
             ((uint32_t *)smem)[i] = (r & 0x807f807fu) | 0x3c003c00u | ((r >> 3) & 0x03800380u);
         }
         __syncthreads();
+        if (DBG == 5 || DBG == 6) {     // fragments read once, from the random fill
+            rd_half(a0, b0, 0, 0, 0, std::true_type{}); rd_half(a0, b0, 0, 0, 1, std::true_type{});
+            rd_half(a1, b1, 0, 1, 0, std::true_type{}); rd_half(a1, b1, 0, 1, 1, std::true_type{});
+            __syncthreads();
+            rd_enable = false;
+        }
     }
     if (nk > 0) {
 #pragma unroll
-        for (int t = 0; t < NSTAGE - 1; ++t) request(t, t);
+        for (int t = 0; t < NSTAGE - 1; ++t) if (DBG != 1 && DBG != 6) request(t, t);
     }
+    // Main loop, "ping-pong" form.  Waves w and w+4 share a SIMD.  Each wave alternates a memory
+    // phase M (request tile kt+3, read all fragments of tile kt from LDS) and a compute phase C
+    // (16 MFMAs), every phase ending in a workgroup barrier; waves 4-7 run half an iteration behind
+    // waves 0-3 (one extra barrier up front, matched by one extra barrier of waves 0-3 at the end),
+    // so on every SIMD one wave feeds the matrix pipe while the other waits on the LDS.
+    //  - tile j is complete before any wave reads it: every wave waits for its own loads of tile
+    //    kt+1 (at most the two newer tiles, 8 loads, outstanding) before each barrier;
+    //  - the stage of tile kt-1 is overwritten by requests issued in M(kt), which every wave starts
+    //    only after a barrier that follows the last fragment read of tile kt-1 (lgkmcnt(0) before
+    //    the barrier that ends each M).
+    static_assert(BK == 32 && NSTAGE == 4, "the ping-pong loop is written for 32-deep tiles and 4 stages");
+    const bool late_group = wave >= 4;
     auto main_loop = [&](auto full) {
-        int stage = 0;                               // kt % NSTAGE
+        if (nk > 0) {
+            __builtin_amdgcn_s_waitcnt(0x0078);          // vmcnt(8): tile 0 has landed
+            __builtin_amdgcn_s_barrier();
+            if (late_group) __builtin_amdgcn_s_barrier();
+        }
+        int stage = 0;                                   // kt % NSTAGE
         for (int kt = 0; kt < nk; ++kt) {
-            // tile kt has landed once at most the (NSTAGE-2) newer requests of 4 loads each are
-            // outstanding; this wave's reads of tile kt-1 must be complete before its stage is reused
-            // (NSTAGE-2) newer tiles of 2*CPW loads each may still be in flight
-            constexpr int INFLIGHT = 2 * CPW * (NSTAGE - 2);
-            static_assert(INFLIGHT >= 0 && INFLIGHT < 16, "vmcnt immediate");
-            __builtin_amdgcn_s_waitcnt(0x0070 | INFLIGHT);      // vmcnt(INFLIGHT) lgkmcnt(0)
-            if (DBG != 6 && DBG != 7) __syncthreads();
             const int prev = stage == 0 ? NSTAGE - 1 : stage - 1;
-            const bool do_req = DBG != 1 && DBG < 5;
-            // 2*KS pieces: request one chunk of tile kt+NSTAGE-1, read half a k-step's fragments of
-            // this tile, multiply half of the previous k-step (tile kt-1's last one to begin with)
-#pragma unroll
-            for (int p = 0; p < 2 * KS; ++p) {
-                const int ks = p >> 1, half = p & 1;
-                if (do_req) request_piece(kt + NSTAGE - 1, prev, p);
-                if (ks & 1) {
-                    rd_half(a1, b1, stage, ks, half, full);
-                    mma_half(a0, b0, half, full);
-                } else {
-                    rd_half(a0, b0, stage, ks, half, full);
-                    mma_half(a1, b1, half, full);
-                }
-                interleave();
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            // ---- M: memory phase
+            if (DBG != 1 && DBG != 6) request(kt + NSTAGE - 1, prev);
+            rd_half(a0, b0, stage, 0, 0, full);
+            rd_half(a0, b0, stage, 0, 1, full);
+            rd_half(a1, b1, stage, 1, 0, full);
+            rd_half(a1, b1, stage, 1, 1, full);
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_waitcnt(0x0078);          // vmcnt(8) lgkmcnt(0)
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            // ---- C: compute phase
+            __builtin_amdgcn_s_setprio(1);
+            mma(a0, b0, full);
+            mma(a1, b1, full);
+            __builtin_amdgcn_s_setprio(0);
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_waitcnt(0x0F78);          // vmcnt(8)
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
             stage = stage == NSTAGE - 1 ? 0 : stage + 1;
         }
-        mma(a1, b1, full);
+        if (nk > 0 && !late_group) __builtin_amdgcn_s_barrier();
     };
     if (__builtin_amdgcn_readfirstlane(Me - m0 >= BM))
         main_loop(std::true_type{});
@@ -462,6 +485,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
             put4(pos, g);
         });
         flush(C);
+    }
+    if (TL && tid == 0 && d.C2) {
+        long long *o = (long long *)d.C2 + (int64_t)pid * 4;
+        o[0] = w_entry; o[1] = wall_clock64(); o[2] = clock64() - t_entry; o[3] = (light ? 1 : 0) + 2 * e + 64 * mti + 1024 * nti;
     }
 }
 
