@@ -49,15 +49,18 @@ constexpr int CPW = BK / 16;                   // 1 KB chunks per wave, operand 
 constexpr int KC_ROW = BK * 2;                 // bytes of one KC row in LDS
 constexpr int KC_G = BK / 8;                   // 16-byte granules per KC row
 constexpr int KC_SWZ_SHIFT = BK == 32 ? 2 : 1; // rows per 256 bytes = 4 (BK 32) or 2 (BK 64)
-constexpr int LIGHT_ROWS = 128;                 // a last m-tile with at most this many rows is scheduled as "light"
+constexpr int LIGHT_BLOCKS = 4;                // an expert with at most this many 32-row blocks is one "light" tile
+constexpr int MAXB = 9;                        // 32-row blocks of a tile when A is a KC operand: 8, or 9 in a "tall" tile
+constexpr int A_ROWS = MAXB * 32;              // rows of the A stage and of the epilogue staging tile
 #ifndef MOE_GEMM_NSTAGE
 #define MOE_GEMM_NSTAGE (MOE_GEMM_BK == 32 ? 4 : 2)
 #endif
 constexpr int NSTAGE = MOE_GEMM_NSTAGE;                      // LDS stages; tiles are requested NSTAGE-1 k-tiles ahead
-constexpr int OPER_BYTES = 256 * BK * 2;       // one operand's k-tile (16 KB)
-constexpr int STAGE_BYTES = 2 * OPER_BYTES;
+constexpr int OPER_BYTES = 256 * BK * 2;       // 256 rows or columns of one operand's k-tile (16 KB)
+constexpr int OPER_A_BYTES = A_ROWS * BK * 2;  // A's part of a stage: room for the ninth block of a tall tile (18 KB)
+constexpr int STAGE_BYTES = OPER_A_BYTES + OPER_BYTES;
 constexpr int CLD = BN + 8;                    // epilogue staging row (elements)
-constexpr int SMEM_BYTES = BM * CLD * 2 > NSTAGE * STAGE_BYTES ? BM * CLD * 2 : NSTAGE * STAGE_BYTES;
+constexpr int SMEM_BYTES = A_ROWS * CLD * 2 > NSTAGE * STAGE_BYTES ? A_ROWS * CLD * 2 : NSTAGE * STAGE_BYTES;
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((address_space(3))) void lds_void;
 
@@ -187,81 +190,205 @@ struct FragAddr {
     }
 };
 
+// Tile plan.  An expert's rows are cut into 32-row MFMA blocks, and its nb blocks into
+// ceil(nb / maxb) m-tiles of nearly equal block counts (maxb = 9 for a KC A operand, else 8): an
+// expert with a few rows more than a multiple of 256 gets "tall" tiles of 9 blocks instead of an
+// extra tile that would stream a whole weight panel for a handful of rows.  An expert with at most
+// LIGHT_BLOCKS blocks is one "light" tile per column of n-tiles.
+// The heavy tiles form one list (expert, then n-tile, then m-tile, so that the m-tiles of one
+// weight panel are neighbours).  The list is cut into 8 contiguous shares of equal work (tile cost x
+// k-tiles: experts differ in size), one per XCD, so that tiles which share a weight panel share an
+// L2; each share is followed by an eighth of the light tiles.  kept[] lives on the device, so a
+// small kernel writes the plan before every GEMM launch:
+//   plan[0..7]   per-share fetch counters (zeroed here, advanced by the GEMM workgroups)
+//   plan[8..16]  start of each share in the tile array (plan[16] = number of tiles)
+//   plan[32 + 4 t ..]  tile t: {expert | blocks << 8 | light << 12, n-tile, first block, kept[expert]}
+// The GEMM kernel is persistent: one workgroup per compute unit takes tiles from the share of its
+// own XCD (workgroup ids go round-robin over the XCDs) until that share is empty.
+constexpr int PLAN_HDR_INTS = 32;
+constexpr int PLAN_THREADS = 1024;
+constexpr int MAX_PLANS = 4;
+
+// Measured cost of a heavy tile by its block count, in half blocks of a full tile's main loop:
+// up to 6 blocks run through the loop that skips blocks (slower per block), 7 and 8 through the
+// full loop, 9 through the tall loop.
+__device__ __forceinline__ int tile_cost(int nblk) { return nblk >= 9 ? 19 : (nblk >= 6 ? 16 : 13); }
+
+struct PlanDesc {
+    const int32_t *kept;
+    int32_t *plan;
+    int E, M, K, nt, rows_from_kept, maxb, cus_per_xcd;
+};
+struct PlanArgs {
+    PlanDesc p[MAX_PLANS];
+};
+
+__global__ __launch_bounds__(PLAN_THREADS) void gemm_plan_kernel(PlanArgs args) {
+    const PlanDesc &p = args.p[blockIdx.x];
+    __shared__ int s_kept[256], s_nb[256], s_hv[256], s_nk[256];
+    __shared__ int s_preH[257], s_preL[257];      // tiles of the experts before e (heavy, light)
+    __shared__ long long s_preW[257];             // work of the heavy tiles of the experts before e
+    __shared__ int s_ts[9], s_sl[9];              // split points of the heavy and of the light list
+    const int tid = threadIdx.x, nt = p.nt;
+    if (tid < p.E) {
+        const int kx = p.kept[tid];
+        const int Mx = p.rows_from_kept ? kx : p.M;
+        const int nb = (Mx + 31) >> 5;
+        const int nk = p.rows_from_kept ? 1 : (kx + BK - 1) / BK;
+        s_kept[tid] = kx;
+        s_nb[tid] = nb;
+        s_hv[tid] = nb > LIGHT_BLOCKS ? (nb + p.maxb - 1) / p.maxb : 0;
+        s_nk[tid] = nk > 0 ? nk : 1;              // never 0: every heavy tile must fall into some share
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int h = 0, l = 0;
+        long long w = 0;
+        for (int e = 0; e < p.E; ++e) {
+            s_preH[e] = h; s_preL[e] = l; s_preW[e] = w;
+            h += s_hv[e] * nt;
+            l += (s_nb[e] > 0 && s_nb[e] <= LIGHT_BLOCKS) ? nt : 0;
+            if (s_hv[e]) {       // one column of the expert's tiles: bx tiles of bb + 1 blocks, the others of bb
+                const int bb = s_nb[e] / s_hv[e], bx = s_nb[e] - bb * s_hv[e];
+                w += (long long)(bx * tile_cost(bb + 1) + (s_hv[e] - bx) * tile_cost(bb)) * s_nk[e] * nt;
+            }
+        }
+        s_preH[p.E] = h; s_preL[p.E] = l; s_preW[p.E] = w;
+    }
+    __syncthreads();
+    const int nH = s_preH[p.E], nL = s_preL[p.E];
+    const long long WH = s_preW[p.E];
+    if (tid <= 8) {
+        // heavy tiles whose preceding work is below th = tid WH / 8
+        const long long th = (tid * WH) >> 3;
+        int res = 0;
+        if (tid == 8) res = nH;
+        else if (th > 0) {
+            int e = 0;
+            while (s_preW[e + 1] < th) ++e;       // s_preW[e] < th <= s_preW[e + 1], so expert e is heavy
+            const int mts = s_hv[e], bb = s_nb[e] / mts, bx = s_nb[e] - bb * mts;
+            const int c1 = tile_cost(bb + 1), c0t = tile_cost(bb);
+            const long long w = (long long)(bx * c1 + (mts - bx) * c0t) * s_nk[e];   // work of one column of its tiles
+            const long long r = th - s_preW[e];                      // 1 .. w nt
+            const int c0 = (int)((r - 1) / w);                       // whole columns of n-tiles before
+            const int rem = (int)(((r - 1) - c0 * w) / s_nk[e]);     // cost inside the column, 0 .. w / nk - 1
+            // tiles of the column whose preceding cost is at most rem
+            int cm = rem < bx * c1 ? rem / c1 + 1 : bx + (rem - bx * c1) / c0t + 1;
+            cm = cm < mts ? cm : mts;
+            res = s_preH[e] + c0 * mts + cm;
+        }
+        // A share is worked off by the cus_per_xcd compute units of one XCD, a tile at a time: a few
+        // tiles beyond a multiple of that number cost a whole extra round, so the split points are
+        // moved to the nearest multiple (this matters when there are only a few rounds).
+        if (tid > 0 && tid < 8) {
+            const int c = p.cus_per_xcd;
+            res = (res + c / 2) / c * c;
+            res = res < nH ? res : nH;
+        }
+        s_ts[tid] = res;
+        s_sl[tid] = (int)(((long long)tid * nL) >> 3);
+    }
+    __syncthreads();
+    if (tid < 8) p.plan[tid] = 0;
+    if (tid <= 8) p.plan[8 + tid] = s_ts[tid] + s_sl[tid];
+    int4 *tiles = (int4 *)(p.plan + PLAN_HDR_INTS);
+    for (int t = tid; t < nH + nL; t += PLAN_THREADS) {
+        const bool light = t >= nH;
+        const int q = light ? t - nH : t;
+        const int *pre = light ? s_preL : s_preH;
+        int lo = 0, hi = p.E;                     // largest e with pre[e] <= q (experts without tiles are skipped)
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (pre[mid] <= q) lo = mid; else hi = mid;
+        }
+        const int e = lo, r = q - pre[e];
+        const int *split = light ? s_sl : s_ts;
+        int x = 0;
+        while (split[x + 1] <= q) ++x;
+        int4 ent;
+        int pos;
+        if (light) {
+            ent = make_int4(e | (s_nb[e] << 8) | (1 << 12), r, 0, s_kept[e]);
+            pos = s_ts[x + 1] + s_sl[x] + (q - s_sl[x]);
+        } else {
+            const int mts = s_hv[e], nti = r / mts, mti = r - nti * mts;   // m fastest
+            // the first nb % mts tiles of a column hold one block more than the others
+            const int bb = s_nb[e] / mts, bx = s_nb[e] - bb * mts;
+            const int nblk = bb + (mti < bx ? 1 : 0), blk0 = mti * bb + (mti < bx ? mti : bx);
+            ent = make_int4(e | (nblk << 8), nti, blk0, s_kept[e]);
+            pos = s_ts[x] + s_sl[x] + (q - s_ts[x]);
+        }
+        tiles[pos] = ent;
+    }
+}
+
 template <bool AXC, bool BXC, int EPI>
-__global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int mt, int nt) {
-    // Tile schedule.  Tiles are "heavy" (a full 256-row tile, or a last tile with more than
-    // LIGHT_ROWS valid rows) or "light" (a last tile with at most LIGHT_ROWS valid rows, in which
-    // whole 32-row MFMA blocks are skipped).  Consecutive workgroup ids go round-robin over the 8
-    // XCDs, so XCD x takes the x-th eighth of the heavy list (tiles that share a weight panel then
-    // share an L2) and, after those, the x-th eighth of the light list: the cheap tiles fill the
-    // last, partial round of the grid instead of idling compute units.  kept[] lives on the
-    // device, so every workgroup derives the lists itself with a short scalar scan over experts.
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
+    __shared__ __attribute__((aligned(1024))) char smem[SMEM_BYTES];
+    __shared__ int s_next[8];                    // the tile fetched by thread 0: its plan entry, then its index
+    const uint32_t smem_addr = (uint32_t)(uintptr_t)(lds_void *)smem;
+    const int tid0 = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
+    const int wm = (wave >> 2) * 128, wn = (wave & 3) * 64;
+    const int jx = wave >> 2;
+    FragAddr<AXC, 4> fa;
+    FragAddr<BXC, 2> fb;
+    fa.init(wm, tid0 & 63);
+    fb.init(wn, tid0 & 63);
+    FragAddr<BXC, 1> fbx;                        // B fragment of the wave's block in a tall tile's ninth block row
+    fbx.init(wn + jx * 32, tid0 & 63);
+    int32_t *plan = (int32_t *)d.plan;
+    const int4 *tiles = (const int4 *)(plan + PLAN_HDR_INTS);
+    const int myx = blockIdx.x & 7;
+    // Tile fetch (thread 0): the workgroup draws tiles from the share of its own XCD until the
+    // share's counter passes its size.  (Taking tiles from other shares at the end was tried and
+    // lost: such a tile finds nothing of its panels in the local L2 and runs at half speed.)
+    int cur_first = 0, cur_cnt = 0;
+    auto fetch_blocking = [&]() {
+        const int t = atomicAdd(plan + myx, 1);
+        return t < cur_cnt ? cur_first + t : -1;
+    };
+    auto publish = [&](int idx, const int4 &ent) {
+        s_next[0] = ent.x; s_next[1] = ent.y; s_next[2] = ent.z; s_next[3] = ent.w; s_next[4] = idx;
+    };
+    // Fetches run two tiles ahead and only during epilogues: the number of the tile after next is
+    // requested and the plan entry of the next tile is loaded while this tile's result is written,
+    // so that no such request is outstanding during a main loop (whose explicit vmcnt waits count
+    // only the loop's own loads).
+    int idx_n = -1;                              // thread 0: the next tile
+    if (tid0 == 0) {
+        cur_first = plan[8 + myx];
+        cur_cnt = plan[9 + myx] - cur_first;
+        const int idx = fetch_blocking();
+        publish(idx, idx >= 0 ? tiles[idx] : make_int4(0, 0, 0, 0));
+        if (idx >= 0) idx_n = fetch_blocking();
+    }
+    __syncthreads();
+
+  for (;;) {
+    // The thread index is made opaque per tile: otherwise the compiler hoists the lane-dependent
+    // address arithmetic of the loaders and of the epilogue out of this loop and keeps it in
+    // registers through the main loop, which has none to spare.
+    int tid = tid0;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63;
     const long long t_entry = TL ? clock64() : 0;
     const long long w_entry = TL ? wall_clock64() : 0;
-    const int pid = blockIdx.x;
-    const int xcd = pid & 7, local = pid >> 3;
-    const int lane_s = threadIdx.x & 63;
-    // per-expert tile counts, 64 experts at a time: lane x of a chunk holds expert chunk*64 + x
-    auto counts_of = [&](int x, int &hv, int &lt) {
-        const int Mx = x < d.E ? (d.rows_from_kept ? d.kept[x] : d.M) : 0;
-        const int remx = Mx % BM;
-        hv = Mx / BM + (remx > LIGHT_ROWS ? 1 : 0);
-        lt = (remx > 0 && remx <= LIGHT_ROWS) ? 1 : 0;
-    };
-    auto wave_sum = [&](int v) {
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-        return v;
-    };
-    auto wave_incl_scan = [&](int v) {
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int t = __shfl_up(v, o);
-            if (lane_s >= o) v += t;
-        }
-        return v;
-    };
-    int nH = 0, nL = 0;
-    for (int c = 0; c < d.E; c += 64) {
-        int hv, lt;
-        counts_of(c + lane_s, hv, lt);
-        nH += wave_sum(hv);
-        nL += wave_sum(lt);
-    }
-    nH *= nt;
-    nL *= nt;
-    const int startH = (int)(((int64_t)xcd * nH) >> 3), cntH = (int)(((int64_t)(xcd + 1) * nH) >> 3) - startH;
-    const int startL = (int)(((int64_t)xcd * nL) >> 3), cntL = (int)(((int64_t)(xcd + 1) * nL) >> 3) - startL;
-    const bool light = local >= cntH;
-    if (light && local - cntH >= cntL) return;
-    int idx = light ? startL + local - cntH : startH + local;     // position in the heavy / light list
-    int e = 0, mti = 0, nti = 0;
-    for (int c = 0; c < d.E; c += 64) {
-        int hv, lt;
-        counts_of(c + lane_s, hv, lt);
-        const int mine = (light ? lt : hv) * nt;
-        const int incl = wave_incl_scan(mine);
-        const unsigned long long hit = __ballot(idx < incl);
-        if (hit) {
-            const int src = __ffsll((long long)hit) - 1;
-            e = c + src;
-            const int r = idx - __shfl(incl - mine, src);
-            const int hve = __shfl(hv, src);
-            if (light) { nti = r; mti = hve; }
-            else { nti = r / hve; mti = r - nti * hve; }   // m fastest: the m-tiles of one weight panel run together
-            break;
-        }
-        idx -= __shfl(incl, 63);
-    }
-    e = __builtin_amdgcn_readfirstlane(e);
-    mti = __builtin_amdgcn_readfirstlane(mti);
-    nti = __builtin_amdgcn_readfirstlane(nti);
-    (void)mt;
+    const int tile_idx = __builtin_amdgcn_readfirstlane(s_next[4]);
+    if (tile_idx < 0) break;
+    const int ent0 = __builtin_amdgcn_readfirstlane(s_next[0]);
+    const int e = ent0 & 255, nblk = (ent0 >> 8) & 15;
+    const bool light = (ent0 >> 12) & 1;
+    const int nti = __builtin_amdgcn_readfirstlane(s_next[1]);
+    const int blk0 = __builtin_amdgcn_readfirstlane(s_next[2]);
+    const int kept = __builtin_amdgcn_readfirstlane(s_next[3]);
+    const long long t_sched = TL ? clock64() : 0;
+    const bool tall = !AXC && nblk == MAXB;
 
-    const int kept = d.kept[e];
     const int Me = d.rows_from_kept ? kept : d.M;
     const int Ke = d.rows_from_kept ? d.K : kept;
-    const int m0 = mti * BM, n0 = nti * BN;
+    const int m0 = blk0 * 32, n0 = nti * BN;
+    const int mlim = Me < m0 + nblk * 32 ? Me : m0 + nblk * 32;     // rows [m0, mlim) are this tile's
 
     const bf16_t *Ap = (const bf16_t *)d.A + (int64_t)e * d.strideA;
     const bf16_t *Bp = (const bf16_t *)d.B + (int64_t)e * d.strideB;
@@ -270,13 +397,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
     const uint32_t b_bytes = (uint32_t)(BXC ? Ke : d.N) * (uint32_t)d.ldb * 2u;
     const i32x4 A = make_rsrc(Ap, a_bytes), B = make_rsrc(Bp, b_bytes);
 
-    __shared__ __attribute__((aligned(1024))) char smem[SMEM_BYTES];
-
-    const uint32_t smem_addr = (uint32_t)(uintptr_t)(lds_void *)smem;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = (wave >> 2) * 128, wn = (wave & 3) * 64;
-
     f32x16 acc[4][2];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -284,22 +404,36 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    // Ninth block row of a tall tile (rows 256..287): its 8 blocks go one to each wave, wave (wm, wn)
+    // taking the column block it already holds a B fragment for: 2 (wn / 64) + wm / 128.
+    f32x16 accx;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) accx[v] = 0.f;
 
     const int nk = (Ke + BK - 1) / BK;
     // Software pipeline.  A k-tile is 32 deep: 2 k-steps of 8 MFMAs per wave.  Tile kt lives in
     // stage kt % NSTAGE and is requested NSTAGE-1 iterations before it is consumed, so up to
     // (NSTAGE-1) x 32 KB are in flight per workgroup.  Each k-step has its own fragment registers
     // (a0/b0, a1/b1), all read in the memory phase that precedes the tile's 16 MFMAs.
-    bf16x8 a0[4], b0[2], a1[4], b1[2];
+    bf16x8 a0[4], b0[2], a1[4], b1[2], ax0, ax1, bx0, bx1;
     Loader la, lb;
-    loader_init<AXC>(la, d.lda, m0, Me, Ke, wave, lane);
+    loader_init<AXC>(la, d.lda, m0, mlim, Ke, wave, lane);
     loader_init<BXC>(lb, d.ldb, n0, d.N, Ke, wave, lane);
-    FragAddr<AXC, 4> fa;
-    FragAddr<BXC, 2> fb;
-    fa.init(wm, lane);
-    fb.init(wn, lane);
+    // tall tile: the two 1 KB chunks of rows 256..287 are loaded by waves 0 and 5 (one wave of each
+    // ping-pong group, on different SIMDs), which therefore have 5 loads per k-tile in flight
+    const int xw = wave == 0 ? 0 : (wave == 5 ? 1 : -1);
+    const bool has_x = !AXC && tall && xw >= 0;
+    uint32_t offx = OOB;
+    int32_t kthrx = 0;
+    if (has_x) {
+        const int row = 256 + 16 * xw + (lane >> 2);
+        const int g = (lane & 3) ^ ((row >> KC_SWZ_SHIFT) & (KC_G - 1));
+        const int gx = m0 + row;
+        offx = gx < mlim ? ((uint32_t)gx * d.lda + g * 8) * 2u : OOB;
+        kthrx = Ke - g * 8;
+    }
     // 32-row blocks of this wave that hold valid rows (4 except in a last, partial m-tile)
-    const int rv = Me - m0 - wm;
+    const int rv = mlim - m0 - wm;
     const int nvi = __builtin_amdgcn_readfirstlane(rv >= 128 ? 4 : (rv <= 0 ? 0 : (rv + 31) >> 5));
     // Fragment reads and MFMAs of one k-step, in halves: half 0 covers a[0], a[1], b[0], b[1] and
     // block rows 0-1, half 1 a[2], a[3] and block rows 2-3.  In a partial m-tile (full = false)
@@ -307,7 +441,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
     bool rd_enable = true;
     auto rd_half = [&](bf16x8(&af)[4], bf16x8(&bf)[2], int stage, int ks, int half, auto full) {
         if ((DBG == 5 || DBG == 6) && !rd_enable) return;
-        const char *ta = smem + stage * STAGE_BYTES, *tb = ta + OPER_BYTES;
+        const char *ta = smem + stage * STAGE_BYTES, *tb = ta + OPER_A_BYTES;
         if (half == 0 && (decltype(full)::value || nvi > 0)) {
 #pragma unroll
             for (int j = 0; j < 2; ++j) bf[j] = fb.read(tb, j, ks);
@@ -337,14 +471,32 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
             const int q = piece - CPW;
             const uint32_t kadd = BXC ? (uint32_t)k0 * d.ldb * 2u : (uint32_t)k0 * 2u;
             const uint32_t voff = k0 < lb.kthr[q] ? lb.off[q] + kadd : OOB;
-            load_to_lds(B, base + OPER_BYTES + (uint32_t)(wave * CPW + q) * 1024u, voff);
+            load_to_lds(B, base + OPER_A_BYTES + (uint32_t)(wave * CPW + q) * 1024u, voff);
         }
+    };
+    auto request_extra = [&](int kt, int stage) {     // tall tiles, waves 0 and 5 only
+        static_assert(BK == 32, "16 rows of 64 bytes per chunk");
+        const int k0 = (DBG == 7 ? 0 : DBG == 8 ? (kt & 7) : kt) * BK;
+        const uint32_t voff = k0 < kthrx ? offx + (uint32_t)k0 * 2u : OOB;
+        load_to_lds(A, smem_addr + stage * STAGE_BYTES + (uint32_t)(256 + 16 * xw) * KC_ROW, voff);
+    };
+    auto rd_extra = [&](int stage) {
+        if ((DBG == 5 || DBG == 6) && !rd_enable) return;
+        const char *ta = smem + stage * STAGE_BYTES, *tb = ta + OPER_A_BYTES;
+        ax0 = fa.read(ta, 8 - (wm >> 5), 0);
+        ax1 = fa.read(ta, 8 - (wm >> 5), 1);
+        bx0 = fbx.read(tb, 0, 0);                 // read again rather than picked from b0 / b1: no VALU work
+        bx1 = fbx.read(tb, 0, 1);                 // between the MFMAs
+    };
+    auto mma_extra = [&](const bf16x8 &bx, const bf16x8 &ax) {
+        accx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bx, ax, accx, 0, 0, 0);
     };
     auto mma = [&](const bf16x8(&af)[4], const bf16x8(&bf)[2], auto full) {
         mma_half(af, bf, 0, full);
         mma_half(af, bf, 1, full);
     };
     auto request = [&](int kt, int stage) {
+        if (DBG == 1 || DBG == 6) return;
 #pragma unroll
         for (int piece = 0; piece < 2 * CPW; ++piece) request_piece(kt, stage, piece);
     };
@@ -354,7 +506,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
     for (int j = 0; j < 2; ++j) b1[j] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
     if (DBG != 0) {      // experiments: operands must look like real data (power draw depends on it)
         for (int i = tid; i < NSTAGE * STAGE_BYTES / 4; i += GEMM_THREADS) {
-            uint32_t r = (uint32_t)i * 2654435761u + (uint32_t)pid;
+            uint32_t r = (uint32_t)i * 2654435761u + (uint32_t)tile_idx;
             r ^= r >> 15; r *= 2246822519u; r ^= r >> 13;
             ((uint32_t *)smem)[i] = (r & 0x807f807fu) | 0x3c003c00u | ((r >> 3) & 0x03800380u);
         }
@@ -366,25 +518,40 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
             rd_enable = false;
         }
     }
-    if (nk > 0) {
-#pragma unroll
-        for (int t = 0; t < NSTAGE - 1; ++t) if (DBG != 1 && DBG != 6) request(t, t);
-    }
     // Main loop, "ping-pong" form.  Waves w and w+4 share a SIMD.  Each wave alternates a memory
     // phase M (request tile kt+3, read all fragments of tile kt from LDS) and a compute phase C
     // (16 MFMAs), every phase ending in a workgroup barrier; waves 4-7 run half an iteration behind
     // waves 0-3 (one extra barrier up front, matched by one extra barrier of waves 0-3 at the end),
     // so on every SIMD one wave feeds the matrix pipe while the other waits on the LDS.
     //  - tile j is complete before any wave reads it: every wave waits for its own loads of tile
-    //    kt+1 (at most the two newer tiles, 8 loads, outstanding) before each barrier;
+    //    kt+1 (at most the two newer tiles outstanding: 8 loads, or 10 in the two waves that load
+    //    the ninth block of a tall tile) before each barrier;
     //  - the stage of tile kt-1 is overwritten by requests issued in M(kt), which every wave starts
     //    only after a barrier that follows the last fragment read of tile kt-1 (lgkmcnt(0) before
     //    the barrier that ends each M).
     static_assert(BK == 32 && NSTAGE == 4, "the ping-pong loop is written for 32-deep tiles and 4 stages");
     const bool late_group = wave >= 4;
-    auto main_loop = [&](auto full) {
+    auto main_loop = [&](auto full, auto tallc) {
+        constexpr bool TALLV = !AXC && decltype(tallc)::value;
+        const bool five = TALLV && DBG != 11 && has_x;   // this wave has 5 loads per k-tile in flight
+        // A wave waits until only the loads of the two newest k-tiles are outstanding.  The two waves
+        // that load the ninth block issue that fifth load in the MFMA phase (the memory phase is the
+        // longer one), so at the end of a memory phase it has not been issued yet for the newest tile.
+        auto wait_end_of_M = [&]() {                     // and lgkmcnt(0)
+            if (five) __builtin_amdgcn_s_waitcnt(0x0070 | 9);
+            else __builtin_amdgcn_s_waitcnt(0x0070 | 8);
+        };
+        auto wait_end_of_C = [&]() {
+            if (five) __builtin_amdgcn_s_waitcnt(0x0F70 | 10);
+            else __builtin_amdgcn_s_waitcnt(0x0F70 | 8);
+        };
         if (nk > 0) {
-            __builtin_amdgcn_s_waitcnt(0x0078);          // vmcnt(8): tile 0 has landed
+#pragma unroll
+            for (int t = 0; t < NSTAGE - 1; ++t) {
+                request(t, t);
+                if (five) request_extra(t, t);
+            }
+            wait_end_of_C();                             // tile 0 has landed
             __builtin_amdgcn_s_barrier();
             if (late_group) __builtin_amdgcn_s_barrier();
         }
@@ -392,34 +559,48 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
         for (int kt = 0; kt < nk; ++kt) {
             const int prev = stage == 0 ? NSTAGE - 1 : stage - 1;
             // ---- M: memory phase
-            if (DBG != 1 && DBG != 6) request(kt + NSTAGE - 1, prev);
+            request(kt + NSTAGE - 1, prev);
             rd_half(a0, b0, stage, 0, 0, full);
             rd_half(a0, b0, stage, 0, 1, full);
             rd_half(a1, b1, stage, 1, 0, full);
             rd_half(a1, b1, stage, 1, 1, full);
+            if (TALLV && DBG != 12) rd_extra(stage);
             __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_waitcnt(0x0078);          // vmcnt(8) lgkmcnt(0)
+            wait_end_of_M();
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
             // ---- C: compute phase
             __builtin_amdgcn_s_setprio(1);
             mma(a0, b0, full);
+            if (five) request_extra(kt + NSTAGE - 1, prev);
+            if (TALLV && DBG != 13) mma_extra(bx0, ax0);
             mma(a1, b1, full);
+            if (TALLV && DBG != 13) mma_extra(bx1, ax1);
             __builtin_amdgcn_s_setprio(0);
             __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_waitcnt(0x0F78);          // vmcnt(8)
+            wait_end_of_C();
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
             stage = stage == NSTAGE - 1 ? 0 : stage + 1;
         }
         if (nk > 0 && !late_group) __builtin_amdgcn_s_barrier();
     };
-    if (__builtin_amdgcn_readfirstlane(Me - m0 >= BM))
-        main_loop(std::true_type{});
+    if (tall)
+        main_loop(std::true_type{}, std::true_type{});
+    else if (nblk >= 7)        // 7 blocks: one zero block costs less than the per-block branches of the partial loop
+        main_loop(std::true_type{}, std::false_type{});
     else
-        main_loop(std::false_type{});
+        main_loop(std::false_type{}, std::false_type{});
     __builtin_amdgcn_s_waitcnt(0x0070);              // nothing may still be writing LDS when it is reused
     __syncthreads();
+    int4 ent_next = make_int4(0, 0, 0, 0);
+    int t_after = 0;
+    if (tid == 0) {                                  // both arrive during the epilogue
+        if (idx_n >= 0) {
+            ent_next = tiles[idx_n];
+            t_after = atomicAdd(plan + myx, 1);
+        }
+    }
 
     // Epilogue.  The MFMAs were issued with the operands swapped (B fragment first), so the
     // accumulators hold the transposed block: lane owns output row m = lane%32 and, per group of
@@ -440,6 +621,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
                     f32x4 v = {acc[i][j][vq * 4], acc[i][j][vq * 4 + 1], acc[i][j][vq * 4 + 2], acc[i][j][vq * 4 + 3]};
                     fn(pos, v);
                 }
+        if (tall) {
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                bf16_t *pos = st + (256 + (lane & 31)) * CLD + wn + jx * 32 + vq * 8 + (lane >> 5) * 4;
+                f32x4 v = {accx[vq * 4], accx[vq * 4 + 1], accx[vq * 4 + 2], accx[vq * 4 + 3]};
+                fn(pos, v);
+            }
+        }
     };
     auto put4 = [](bf16_t *pos, const f32x4 &v) {
         bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
@@ -447,12 +636,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
     };
     auto flush = [&](bf16_t *out) {
         __syncthreads();
-#pragma unroll
-        for (int p = 0; p < 16; ++p) {
+        auto pass = [&](int p) {
             const int row = (tid >> 5) + 16 * p, gm = m0 + row, gn = n0 + (tid & 31) * 8;
             const u32x4 v = *(const u32x4 *)(st + row * CLD + (tid & 31) * 8);
-            if (gm < Me && gn < d.N) *(u32x4 *)(out + (int64_t)gm * d.ldc + gn) = v;
-        }
+            if (gm < mlim && gn < d.N) *(u32x4 *)(out + (int64_t)gm * d.ldc + gn) = v;
+        };
+#pragma unroll
+        for (int p = 0; p < 16; ++p) pass(p);
+        if (tall) { pass(16); pass(17); }
     };
     if (EPI == EPI_STORE) {
         for_each_quad([&](bf16_t *pos, const f32x4 &v) { put4(pos, v); });
@@ -470,13 +661,15 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
         flush(C);
     } else {
         const bf16_t *Zin = (const bf16_t *)d.Zin + (int64_t)e * d.strideC;
-#pragma unroll
-        for (int p = 0; p < 16; ++p) {
+        auto zpass = [&](int p) {
             const int row = (tid >> 5) + 16 * p, gm = m0 + row, gn = n0 + (tid & 31) * 8;
             u32x4 v = {0u, 0u, 0u, 0u};
-            if (gm < Me && gn < d.N) v = *(const u32x4 *)(Zin + (int64_t)gm * d.ldc + gn);
+            if (gm < mlim && gn < d.N) v = *(const u32x4 *)(Zin + (int64_t)gm * d.ldc + gn);
             *(u32x4 *)(st + row * CLD + (tid & 31) * 8) = v;
-        }
+        };
+#pragma unroll
+        for (int p = 0; p < 16; ++p) zpass(p);
+        if (tall) { zpass(16); zpass(17); }
         __syncthreads();
         for_each_quad([&](bf16_t *pos, const f32x4 &v) {
             const bf16x4 z = *(const bf16x4 *)pos;
@@ -487,35 +680,88 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d, int
         flush(C);
     }
     if (TL && tid == 0 && d.C2) {
-        long long *o = (long long *)d.C2 + (int64_t)pid * 4;
-        o[0] = w_entry; o[1] = wall_clock64(); o[2] = clock64() - t_entry; o[3] = (light ? 1 : 0) + 2 * e + 64 * mti + 1024 * nti;
+        long long *o = (long long *)d.C2 + (int64_t)tile_idx * 4;
+        o[0] = w_entry; o[1] = wall_clock64(); o[2] = clock64() - t_entry;
+        o[3] = nblk | (e << 8) | (myx << 20) | ((light ? 1 : 0) << 24) | ((long long)(t_sched - t_entry) << 32);
     }
+    // the staging tile is reused by the next tile; s_next was last read before the main loop
+    if (tid == 0) {
+        publish(idx_n, ent_next);
+        idx_n = (idx_n >= 0 && t_after < cur_cnt) ? cur_first + t_after : -1;
+    }
+    __syncthreads();
+  }
+}
+
+static int num_compute_units() {
+    static int cus = 0;                          // same value from every thread that races here
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            n <= 0)
+            n = 256;
+        cus = n;
+    }
+    return cus;
+}
+
+size_t gemm_bf16_plan_bytes(const GemmDesc &d) {
+    const int64_t mt = (d.M + BM - 1) / BM, nt = (d.N + BN - 1) / BN;
+    return (size_t)(PLAN_HDR_INTS * 4 + 16 * (int64_t)d.E * mt * nt + 255) / 256 * 256;
+}
+
+moe_status_t launch_gemm_bf16_plans(const GemmDesc *descs, int n, hipStream_t s) {
+    if (n < 1 || n > MAX_PLANS) {
+        set_error("gemm_bf16: %d plans in one launch", n);
+        return MOE_ERR_INVALID_ARG;
+    }
+    PlanArgs args = {};
+    for (int i = 0; i < n; ++i) {
+        const GemmDesc &d = descs[i];
+        if (d.plan == nullptr || d.E > 256) {
+            set_error("gemm_bf16: no plan buffer, or more than 256 experts");
+            return MOE_ERR_INVALID_ARG;
+        }
+        PlanDesc &p = args.p[i];
+        p.kept = d.kept; p.plan = (int32_t *)d.plan;
+        p.E = d.E; p.M = d.M; p.K = d.K; p.nt = (d.N + BN - 1) / BN;
+        p.rows_from_kept = d.rows_from_kept; p.maxb = d.a_xc ? 8 : MAXB;
+        p.cus_per_xcd = num_compute_units() / 8 > 0 ? num_compute_units() / 8 : 1;
+    }
+    hipLaunchKernelGGL(gemm_plan_kernel, dim3(n), dim3(PLAN_THREADS), 0, s, args);
+    return check_launch("gemm_plan");
 }
 
 template <bool AXC, bool BXC>
-static void launch_epi(const GemmDesc &d, int mt, int nt, hipStream_t s) {
-    dim3 grid((unsigned)((int64_t)d.E * mt * nt + 16)), block(GEMM_THREADS);
+static void launch_epi(const GemmDesc &d, hipStream_t s) {
+    // persistent: one workgroup per compute unit (the LDS footprint allows no second one)
+    dim3 grid((unsigned)num_compute_units()), block(GEMM_THREADS);
     switch (d.epi) {
         case EPI_STORE:
-            hipLaunchKernelGGL((gemm_bf16_kernel<AXC, BXC, EPI_STORE>), grid, block, 0, s, d, mt, nt);
+            hipLaunchKernelGGL((gemm_bf16_kernel<AXC, BXC, EPI_STORE>), grid, block, 0, s, d);
             break;
         case EPI_GELU:
-            hipLaunchKernelGGL((gemm_bf16_kernel<AXC, BXC, EPI_GELU>), grid, block, 0, s, d, mt, nt);
+            hipLaunchKernelGGL((gemm_bf16_kernel<AXC, BXC, EPI_GELU>), grid, block, 0, s, d);
             break;
         default:
-            hipLaunchKernelGGL((gemm_bf16_kernel<AXC, BXC, EPI_DGELU>), grid, block, 0, s, d, mt, nt);
+            hipLaunchKernelGGL((gemm_bf16_kernel<AXC, BXC, EPI_DGELU>), grid, block, 0, s, d);
             break;
     }
 }
 
+// The plan in d.plan must have been written (launch_gemm_bf16_plans) earlier on the same stream,
+// for this descriptor's kept, E, M, N, K, rows_from_kept and A layout; a plan serves one launch.
 moe_status_t launch_gemm_bf16(const GemmDesc &d, hipStream_t s) {
-    const int mt = (d.M + BM - 1) / BM, nt = (d.N + BN - 1) / BN;
+    if (d.plan == nullptr) {
+        set_error("gemm_bf16: no plan");
+        return MOE_ERR_INVALID_ARG;
+    }
     if (!d.a_xc && d.b_xc)
-        launch_epi<false, true>(d, mt, nt, s);      // forward: A [M,K], B [K,N]
+        launch_epi<false, true>(d, s);      // forward: A [M,K], B [K,N]
     else if (!d.a_xc && !d.b_xc)
-        launch_epi<false, false>(d, mt, nt, s);     // data gradient: A [M,K], B [N,K]
+        launch_epi<false, false>(d, s);     // data gradient: A [M,K], B [N,K]
     else if (d.a_xc && d.b_xc)
-        launch_epi<true, true>(d, mt, nt, s);       // weight gradient: A [K,M], B [K,N]
+        launch_epi<true, true>(d, s);       // weight gradient: A [K,M], B [K,N]
     else {
         set_error("gemm_bf16: operand layout combination not built");
         return MOE_ERR_UNSUPPORTED;

@@ -107,11 +107,62 @@ static bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
 static size_t round256(size_t v) { return (v + 255) / 256 * 256; }
 static size_t dz_bytes(const moe_shape_t *sh) { return round256((size_t)sh->E * sh->C * sh->f * esize(sh)); }
 
+// The six grouped GEMMs of the expert FFN (bf16 path: each needs a tile plan in the workspace).
+enum { G_FWD1, G_FWD2, G_DH, G_DW2, G_DW1, G_DD };
+static GemmDesc ffn_gemm(const moe_shape_t &s, int which) {
+    GemmDesc g = {};
+    g.E = s.E; g.act = s.act; g.epi = EPI_STORE;
+    const int32_t C = (int32_t)s.C;
+    switch (which) {
+        case G_FWD1:   // z = buf w1, hact = act(z)        A = buf [M,h], B = w1 [h,f] = [K,N]
+            g.strideA = s.C * s.h; g.strideB = (int64_t)s.h * s.f; g.strideC = s.C * s.f;
+            g.M = C; g.N = s.f; g.K = s.h; g.lda = s.h; g.ldb = s.f; g.ldc = s.f;
+            g.a_xc = 0; g.b_xc = 1; g.rows_from_kept = 1; g.epi = EPI_GELU;
+            break;
+        case G_FWD2:   // y = hact w2                      A = hact [M,f], B = w2 [f,h] = [K,N]
+            g.strideA = s.C * s.f; g.strideB = (int64_t)s.f * s.h; g.strideC = s.C * s.h;
+            g.M = C; g.N = s.h; g.K = s.f; g.lda = s.f; g.ldb = s.h; g.ldc = s.h;
+            g.a_xc = 0; g.b_xc = 1; g.rows_from_kept = 1;
+            break;
+        case G_DH:     // d_z = (d_y w2^T) * act'(z)       A = d_y [M,h], B = w2 [f,h] = [N,K]
+            g.strideA = s.C * s.h; g.strideB = (int64_t)s.f * s.h; g.strideC = s.C * s.f;
+            g.M = C; g.N = s.f; g.K = s.h; g.lda = s.h; g.ldb = s.h; g.ldc = s.f;
+            g.a_xc = 0; g.b_xc = 0; g.rows_from_kept = 1; g.epi = EPI_DGELU;
+            break;
+        case G_DW2:    // d_w2 = hact^T d_y                A = hact [K=rows, M=f], B = d_y [K=rows, N=h]
+            g.strideA = s.C * s.f; g.strideB = s.C * s.h; g.strideC = (int64_t)s.f * s.h;
+            g.M = s.f; g.N = s.h; g.K = C; g.lda = s.f; g.ldb = s.h; g.ldc = s.h;
+            g.a_xc = 1; g.b_xc = 1; g.rows_from_kept = 0;
+            break;
+        case G_DW1:    // d_w1 = buf^T d_z                 A = buf [K=rows, M=h], B = d_z [K=rows, N=f]
+            g.strideA = s.C * s.h; g.strideB = s.C * s.f; g.strideC = (int64_t)s.h * s.f;
+            g.M = s.h; g.N = s.f; g.K = C; g.lda = s.h; g.ldb = s.f; g.ldc = s.f;
+            g.a_xc = 1; g.b_xc = 1; g.rows_from_kept = 0;
+            break;
+        default:       // d_buf = d_z w1^T                 A = d_z [M,f], B = w1 [h,f] = [N,K]
+            g.strideA = s.C * s.f; g.strideB = (int64_t)s.h * s.f; g.strideC = s.C * s.h;
+            g.M = C; g.N = s.h; g.K = s.f; g.lda = s.f; g.ldb = s.f; g.ldc = s.h;
+            g.a_xc = 0; g.b_xc = 0; g.rows_from_kept = 1;
+            break;
+    }
+    return g;
+}
+static size_t ffn_plan_bytes(const moe_shape_t *sh, int first, int last) {
+    if (sh->dtype != MOE_BF16) return 0;
+    size_t n = 0;
+    for (int w = first; w <= last; ++w) n += gemm_bf16_plan_bytes(ffn_gemm(*sh, w));
+    return n;
+}
+static size_t ffn_fwd_ws_bytes(const moe_shape_t *sh) { return ffn_plan_bytes(sh, G_FWD1, G_FWD2); }
+static size_t ffn_bwd_ws_bytes(const moe_shape_t *sh) { return dz_bytes(sh) + ffn_plan_bytes(sh, G_DH, G_DD); }
+
 static size_t ws_bytes_checked(const moe_shape_t *sh, int for_backward) {
-    size_t fwd = gate_ws_bytes(sh);
-    if (!for_backward) return fwd;
-    size_t bwd = dz_bytes(sh) + round256(gate_bwd_ws_bytes(sh));
-    return fwd > bwd ? fwd : bwd;
+    size_t need = gate_ws_bytes(sh);
+    if (ffn_fwd_ws_bytes(sh) > need) need = ffn_fwd_ws_bytes(sh);
+    if (!for_backward) return need;
+    if (ffn_bwd_ws_bytes(sh) > need) need = ffn_bwd_ws_bytes(sh);
+    if (round256(gate_bwd_ws_bytes(sh)) > need) need = round256(gate_bwd_ws_bytes(sh));
+    return need;
 }
 
 static moe_status_t check_ws(const char *fn, const void *ws, size_t have, size_t need) {
@@ -195,8 +246,6 @@ moe_status_t moe_dispatch(const moe_shape_t *shape, const void *x, const int32_t
 moe_status_t moe_expert_ffn_fwd(const moe_shape_t *shape, const void *buf, const void *w1, const void *w2,
                                 const int32_t *kept, void *z_save, void *hact, void *y, void *ws, size_t ws_bytes,
                                 void *stream) {
-    (void)ws;
-    (void)ws_bytes;
     moe_status_t st = check_shape(shape);
     if (st != MOE_OK) return st;
     REQUIRE_PTR(buf);
@@ -206,21 +255,22 @@ moe_status_t moe_expert_ffn_fwd(const moe_shape_t *shape, const void *buf, const
     OPTIONAL_PTR(z_save);
     REQUIRE_PTR(hact);
     REQUIRE_PTR(y);
+    st = check_ws("moe_expert_ffn_fwd", ws, ws_bytes, ffn_fwd_ws_bytes(shape));
+    if (st != MOE_OK) return st;
     const moe_shape_t &s = *shape;
     const bool bf = s.dtype == MOE_BF16;
-    GemmDesc g1 = {};
-    g1.A = buf; g1.B = w1; g1.C = hact; g1.C2 = z_save; g1.kept = kept;
-    g1.strideA = s.C * s.h; g1.strideB = (int64_t)s.h * s.f; g1.strideC = s.C * s.f;
-    g1.M = (int32_t)s.C; g1.N = s.f; g1.K = s.h; g1.lda = s.h; g1.ldb = s.f; g1.ldc = s.f; g1.E = s.E;
-    g1.a_xc = 0; g1.b_xc = 1; g1.rows_from_kept = 1; g1.epi = EPI_GELU; g1.act = s.act;
-    st = bf ? launch_gemm_bf16(g1, (hipStream_t)stream) : launch_gemm_f32(g1, (hipStream_t)stream);
-    if (st != MOE_OK) return st;
-    GemmDesc g2 = {};
-    g2.A = hact; g2.B = w2; g2.C = y; g2.kept = kept;
-    g2.strideA = s.C * s.f; g2.strideB = (int64_t)s.f * s.h; g2.strideC = s.C * s.h;
-    g2.M = (int32_t)s.C; g2.N = s.h; g2.K = s.f; g2.lda = s.f; g2.ldb = s.h; g2.ldc = s.h; g2.E = s.E;
-    g2.a_xc = 0; g2.b_xc = 1; g2.rows_from_kept = 1; g2.epi = EPI_STORE; g2.act = s.act;
-    return bf ? launch_gemm_bf16(g2, (hipStream_t)stream) : launch_gemm_f32(g2, (hipStream_t)stream);
+    hipStream_t hs = (hipStream_t)stream;
+    GemmDesc g[2] = {ffn_gemm(s, G_FWD1), ffn_gemm(s, G_FWD2)};
+    g[0].A = buf; g[0].B = w1; g[0].C = hact; g[0].C2 = z_save; g[0].kept = kept;
+    g[1].A = hact; g[1].B = w2; g[1].C = y; g[1].kept = kept;
+    if (bf) {
+        char *pl = (char *)ws;
+        for (int i = 0; i < 2; ++i) { g[i].plan = pl; pl += gemm_bf16_plan_bytes(g[i]); }
+        if ((st = launch_gemm_bf16_plans(g, 2, hs)) != MOE_OK) return st;
+    }
+    for (int i = 0; i < 2; ++i)
+        if ((st = bf ? launch_gemm_bf16(g[i], hs) : launch_gemm_f32(g[i], hs)) != MOE_OK) return st;
+    return MOE_OK;
 }
 
 moe_status_t moe_combine(const moe_shape_t *shape, const void *y, const int32_t *expert, const int32_t *slot,
@@ -264,41 +314,26 @@ moe_status_t moe_expert_ffn_bwd(const moe_shape_t *shape, const void *d_y, const
     REQUIRE_PTR(d_buf);
     REQUIRE_PTR(d_w1);
     REQUIRE_PTR(d_w2);
-    st = check_ws("moe_expert_ffn_bwd", ws, ws_bytes, dz_bytes(shape));
+    st = check_ws("moe_expert_ffn_bwd", ws, ws_bytes, ffn_bwd_ws_bytes(shape));
     if (st != MOE_OK) return st;
     const moe_shape_t &s = *shape;
     const bool bf = s.dtype == MOE_BF16;
     hipStream_t hs = (hipStream_t)stream;
     void *d_z = ws;
-    auto run = [&](const GemmDesc &g) { return bf ? launch_gemm_bf16(g, hs) : launch_gemm_f32(g, hs); };
-    // d_z = (d_y w2^T) * act'(z)          A = d_y [M,h], B = w2 [f,h] = [N,K]
-    GemmDesc g = {};
-    g.A = d_y; g.B = w2; g.C = d_z; g.Zin = z_save; g.kept = kept;
-    g.strideA = s.C * s.h; g.strideB = (int64_t)s.f * s.h; g.strideC = s.C * s.f;
-    g.M = (int32_t)s.C; g.N = s.f; g.K = s.h; g.lda = s.h; g.ldb = s.h; g.ldc = s.f; g.E = s.E;
-    g.a_xc = 0; g.b_xc = 0; g.rows_from_kept = 1; g.epi = EPI_DGELU; g.act = s.act;
-    if ((st = run(g)) != MOE_OK) return st;
-    // d_w2 = hact^T d_y                   A = hact [K=rows, M=f], B = d_y [K=rows, N=h]
-    g = GemmDesc{};
-    g.A = hact; g.B = d_y; g.C = d_w2; g.kept = kept;
-    g.strideA = s.C * s.f; g.strideB = s.C * s.h; g.strideC = (int64_t)s.f * s.h;
-    g.M = s.f; g.N = s.h; g.K = (int32_t)s.C; g.lda = s.f; g.ldb = s.h; g.ldc = s.h; g.E = s.E;
-    g.a_xc = 1; g.b_xc = 1; g.rows_from_kept = 0; g.epi = EPI_STORE; g.act = s.act;
-    if ((st = run(g)) != MOE_OK) return st;
-    // d_w1 = buf^T d_z                    A = buf [K=rows, M=h], B = d_z [K=rows, N=f]
-    g = GemmDesc{};
-    g.A = buf; g.B = d_z; g.C = d_w1; g.kept = kept;
-    g.strideA = s.C * s.h; g.strideB = s.C * s.f; g.strideC = (int64_t)s.h * s.f;
-    g.M = s.h; g.N = s.f; g.K = (int32_t)s.C; g.lda = s.h; g.ldb = s.f; g.ldc = s.f; g.E = s.E;
-    g.a_xc = 1; g.b_xc = 1; g.rows_from_kept = 0; g.epi = EPI_STORE; g.act = s.act;
-    if ((st = run(g)) != MOE_OK) return st;
-    // d_buf = d_z w1^T                    A = d_z [M,f], B = w1 [h,f] = [N,K]
-    g = GemmDesc{};
-    g.A = d_z; g.B = w1; g.C = d_buf; g.kept = kept;
-    g.strideA = s.C * s.f; g.strideB = (int64_t)s.h * s.f; g.strideC = s.C * s.h;
-    g.M = (int32_t)s.C; g.N = s.h; g.K = s.f; g.lda = s.f; g.ldb = s.f; g.ldc = s.h; g.E = s.E;
-    g.a_xc = 0; g.b_xc = 0; g.rows_from_kept = 1; g.epi = EPI_STORE; g.act = s.act;
-    return run(g);
+    GemmDesc g[4] = {ffn_gemm(s, G_DH), ffn_gemm(s, G_DW2), ffn_gemm(s, G_DW1), ffn_gemm(s, G_DD)};
+    g[0].A = d_y; g[0].B = w2; g[0].C = d_z; g[0].Zin = z_save;
+    g[1].A = hact; g[1].B = d_y; g[1].C = d_w2;
+    g[2].A = buf; g[2].B = d_z; g[2].C = d_w1;
+    g[3].A = d_z; g[3].B = w1; g[3].C = d_buf;
+    for (int i = 0; i < 4; ++i) g[i].kept = kept;
+    if (bf) {
+        char *pl = (char *)ws + dz_bytes(shape);
+        for (int i = 0; i < 4; ++i) { g[i].plan = pl; pl += gemm_bf16_plan_bytes(g[i]); }
+        if ((st = launch_gemm_bf16_plans(g, 4, hs)) != MOE_OK) return st;
+    }
+    for (int i = 0; i < 4; ++i)
+        if ((st = bf ? launch_gemm_bf16(g[i], hs) : launch_gemm_f32(g[i], hs)) != MOE_OK) return st;
+    return MOE_OK;
 }
 
 moe_status_t moe_dispatch_bwd(const moe_shape_t *shape, const void *d_buf, const int32_t *expert, const int32_t *slot,

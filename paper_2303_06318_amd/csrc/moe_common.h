@@ -57,9 +57,13 @@ struct GemmDesc {
     int32_t lda, ldb, ldc;
     int32_t E;
     int32_t a_xc, b_xc, rows_from_kept, epi, act;
+    void *plan;       // bf16 path: device buffer of gemm_bf16_plan_bytes() bytes holding this launch's tile plan
 };
 
 moe_status_t launch_gemm_f32(const GemmDesc &d, hipStream_t s);
+// bf16 path: write the tile plans of up to 4 GEMMs in one small launch, then launch each GEMM once
+size_t gemm_bf16_plan_bytes(const GemmDesc &d);
+moe_status_t launch_gemm_bf16_plans(const GemmDesc *descs, int n, hipStream_t s);
 moe_status_t launch_gemm_bf16(const GemmDesc &d, hipStream_t s);
 
 }  // namespace moe

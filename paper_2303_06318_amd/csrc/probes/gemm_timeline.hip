@@ -1,4 +1,4 @@
-// Timeline of one launch of the grouped bf16 GEMM: when each workgroup started and ended (constant
+// Timeline of one launch of the grouped bf16 GEMM: when each tile started and ended (constant
 // 100 MHz wall clock) and how many shader cycles it took, which gives the shader clock the chip
 // actually ran at, the number of rounds, and the gaps between rounds.  Built together with the
 // kernel source, with the timeline stamps and optionally one of the ablation variants switched on:
@@ -91,21 +91,33 @@ int main(int argc, char **argv) {
         g.B = A; g.strideA = (int64_t)C * h; g.strideB = (int64_t)C * h; g.strideC = (int64_t)h * f;
         g.M = h; g.N = f; g.K = C; g.lda = h; g.ldb = h; g.ldc = f; g.a_xc = 1; g.b_xc = 1; g.rows_from_kept = 0;
     }
-    const int max_wg = 4096;                       // more than any grid of these shapes
-    long long *stamps;
-    CHECK(hipMalloc(&stamps, (size_t)max_wg * 32));
-    CHECK(hipMemset(stamps, 0, (size_t)max_wg * 32));
+    void *plan;
+    CHECK(hipMalloc(&plan, gemm_bf16_plan_bytes(g)));
+    g.plan = plan;
+    const int max_wg = 8192;                       // more than the tiles of any of these shapes
+    const int it = 20;                             // timed launches, each with its own stamp buffer
+    long long *stamps_all;
+    CHECK(hipMalloc(&stamps_all, (size_t)it * max_wg * 32));
+    CHECK(hipMemset(stamps_all, 0, (size_t)it * max_wg * 32));
+    long long *stamps = stamps_all + (size_t)(it - 1) * max_wg * 4;
+    bool stamped = false;
 #if defined(MOE_GEMM_TL) && MOE_GEMM_TL
-    g.C2 = stamps;
+    stamped = true;
 #endif
     hipEvent_t e0, e1;
     CHECK(hipEventCreate(&e0));
     CHECK(hipEventCreate(&e1));
-    for (int i = 0; i < 3; ++i) launch_gemm_bf16(g, 0);
+    for (int i = 0; i < 3; ++i) {
+        launch_gemm_bf16_plans(&g, 1, 0);
+        launch_gemm_bf16(g, 0);
+    }
     CHECK(hipDeviceSynchronize());
-    const int it = 20;
     CHECK(hipEventRecord(e0, 0));
-    for (int i = 0; i < it; ++i) launch_gemm_bf16(g, 0);
+    for (int i = 0; i < it; ++i) {
+        if (stamped) g.C2 = stamps_all + (size_t)i * max_wg * 4;
+        launch_gemm_bf16_plans(&g, 1, 0);
+        launch_gemm_bf16(g, 0);
+    }
     CHECK(hipEventRecord(e1, 0));
     CHECK(hipEventSynchronize(e1));
     float ms;
@@ -116,10 +128,10 @@ int main(int argc, char **argv) {
 
     std::vector<long long> tl((size_t)max_wg * 4);
     CHECK(hipMemcpy(tl.data(), stamps, (size_t)max_wg * 32, hipMemcpyDeviceToHost));
-    struct Rec { long long start, end, cycles; };
+    struct Rec { long long start, end, cycles, id; };
     std::vector<Rec> recs;
     for (int i = 0; i < max_wg; ++i)
-        if (tl[4 * i]) recs.push_back({tl[4 * i], tl[4 * i + 1], tl[4 * i + 2]});
+        if (tl[4 * i]) recs.push_back({tl[4 * i], tl[4 * i + 1], tl[4 * i + 2], tl[4 * i + 3]});
     if (recs.empty()) {
         printf("no stamps (build with -DMOE_GEMM_TL=1)\n");
         return 0;
@@ -128,8 +140,29 @@ int main(int argc, char **argv) {
     const long long t0 = recs[0].start;
     long long tend = 0;
     for (auto &r : recs) tend = std::max(tend, r.end);
-    printf("last launch: %zu workgroups, span %.1f us\n", recs.size(), (tend - t0) / 100.0);
-    printf("round  start_us  end_us  duration_us  shader_cycles  shader_MHz   (medians over 256 workgroups by start time)\n");
+    printf("last launch: %zu tiles, span %.1f us\n", recs.size(), (tend - t0) / 100.0);
+    {
+        std::vector<long long> tp((size_t)it * max_wg * 4);
+        CHECK(hipMemcpy(tp.data(), stamps_all, (size_t)it * max_wg * 32, hipMemcpyDeviceToHost));
+        long long first = 0, pend = 0;
+        printf("launch: first entry, last exit (us since the first launch's first entry), gap to the previous launch\n");
+        for (int l = 0; l < it; ++l) {
+            long long lo = 1LL << 62, hi = 0;
+            for (int i = 0; i < max_wg; ++i) {
+                const long long *r = &tp[((size_t)l * max_wg + i) * 4];
+                if (r[0]) { lo = std::min(lo, r[0]); hi = std::max(hi, r[1]); }
+            }
+            if (l == 0) first = lo;
+            printf("  %2d: %8.1f %8.1f  %6.1f\n", l, (lo - first) / 100.0, (hi - first) / 100.0, l ? (lo - pend) / 100.0 : 0.0);
+            pend = hi;
+        }
+        std::vector<double> du;
+        for (auto &r : recs) du.push_back((r.end - r.start) / 100.0);
+        std::sort(du.begin(), du.end());
+        printf("tile duration us: min %.1f  p10 %.1f  median %.1f  p90 %.1f  max %.1f\n", du[0], du[du.size() / 10], du[du.size() / 2],
+               du[du.size() * 9 / 10], du.back());
+    }
+    printf("round  start_us  end_us  duration_us  shader_cycles  shader_MHz   (medians over 256 tiles by start time)\n");
     for (size_t q = 0; q < recs.size(); q += 256) {
         const size_t n = std::min<size_t>(256, recs.size() - q);
         std::vector<double> st, en, du, cy, mhz;
@@ -142,10 +175,33 @@ int main(int argc, char **argv) {
             mhz.push_back(r.end > r.start ? 100.0 * r.cycles / (r.end - r.start) : 0.0);
         }
         auto med = [](std::vector<double> &v) { std::sort(v.begin(), v.end()); return v[v.size() / 2]; };
-        printf("%5zu  %8.1f  %6.1f  %11.1f  %13.0f  %10.0f   (%zu workgroups)\n", q / 256, med(st), med(en), med(du), med(cy),
+        printf("%5zu  %8.1f  %6.1f  %11.1f  %13.0f  %10.0f   (%zu tiles)\n", q / 256, med(st), med(en), med(du), med(cy),
                med(mhz), n);
     }
-    // workgroups in flight, sampled every 20 us
+    // by blocks per tile, and the time each XCD's last workgroup ended
+    for (int nb = 1; nb <= 9; ++nb) {
+        std::vector<double> du, cy;
+        for (auto &r : recs)
+            if ((r.id & 255) == nb) { du.push_back((r.end - r.start) / 100.0); cy.push_back((double)r.cycles); }
+        if (du.empty()) continue;
+        std::sort(du.begin(), du.end());
+        std::sort(cy.begin(), cy.end());
+        std::vector<double> sc;
+        for (auto &r : recs)
+            if ((r.id & 255) == nb) sc.push_back((double)(r.id >> 32));
+        std::sort(sc.begin(), sc.end());
+        printf("tiles of %d blocks: %zu, duration us median %.1f max %.1f, shader cycles median %.0f (schedule %.0f)\n", nb, du.size(),
+               du[du.size() / 2], du.back(), cy[cy.size() / 2], sc[sc.size() / 2]);
+    }
+    printf("last exit per XCD (us), tiles:");
+    for (int x = 0; x < 8; ++x) {
+        long long hi = 0; int n = 0;
+        for (auto &r : recs)
+            if (((r.id >> 20) & 15) == x) { hi = std::max(hi, r.end); ++n; }
+        printf(" %.1f (%d)", (hi - t0) / 100.0, n);
+    }
+    printf("\n");
+    // tiles in flight, sampled every 20 us
     printf("in flight:");
     for (long long t = t0; t < tend; t += 2000) {
         int c = 0;

@@ -26,6 +26,10 @@ CASES = {
     "bf16_one_expert": synth.scaled(W["cfg5_6p7b_tp4_fwdbwd"], T=600, h=264, f=328, E=1, capacity_factor=0.9),
     "bf16_bwd_E64": synth.scaled(W["cfg4_skewed_fwd"], T=3000, h=264, f=136, E=64, backward=True),
     "bf16_bwd_E200": synth.scaled(W["cfg5_6p7b_tp4_fwdbwd"], T=2100, h=136, f=72, E=200, capacity_factor=2.0),
+    # full experts hold 275 rows = 9 MFMA blocks (one 9-block GEMM tile), the others a ragged 6-9 blocks
+    "bf16_bwd_9blocks": synth.scaled(W["cfg5_6p7b_tp4_fwdbwd"], T=1100, h=264, f=328, E=4, capacity_factor=1.0),
+    # 560 rows = 18 blocks = two 9-block tiles; 600 rows = 19 blocks = 7 + 6 + 6
+    "bf16_bwd_18blocks": synth.scaled(W["cfg5_6p7b_tp4_fwdbwd"], T=1120, h=136, f=264, E=2, capacity_factor=1.0),
 }
 
 
@@ -85,7 +89,8 @@ def test_forward_parity(orc, name):
     assert (out[slot < 0] == 0).all()
 
 
-@pytest.mark.parametrize("name", ["cfg5_small", "f32_bwd", "bf16_one_expert", "bf16_bwd_E64", "bf16_bwd_E200"])
+@pytest.mark.parametrize("name", ["cfg5_small", "f32_bwd", "bf16_one_expert", "bf16_bwd_E64", "bf16_bwd_E200",
+                                  "bf16_bwd_9blocks", "bf16_bwd_18blocks"])
 @pytest.mark.parametrize("act", [moe.MOE_GELU_ERF, moe.MOE_GELU_TANH])
 def test_backward_parity(orc, name, act):
     wl = CASES[name]
