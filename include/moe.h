@@ -121,7 +121,10 @@ moe_status_t moe_dispatch(const moe_shape_t *shape, const void *x, const int32_t
  *   for r < kept[e]:  z = buf[e,r,:] w1[e] ;  hact = GeLU(z) ;  y[e,r,:] = hact w2[e]
  * Rows r >= kept[e] of hact, z_save and y are not written.
  *   buf [E,C,h], w1 [E,h,f], w2 [E,f,h], kept [E], hact [E,C,f] (out, needed by backward),
- *   z_save [E,C,f] or NULL (pre-activation, needed by backward), y [E,C,h].
+ *   z_save [E,C,f] or NULL (out, needed by backward: it receives GeLU'(z), the only function of
+ *   the pre-activation the backward pass uses, so that backward does not evaluate erf again),
+ *   y [E,C,h].
+ * bf16: uses moe_workspace_bytes(shape, 0) bytes of workspace (tile plans of the two GEMMs).
  */
 moe_status_t moe_expert_ffn_fwd(const moe_shape_t *shape, const void *buf, const void *w1, const void *w2,
                                 const int32_t *kept, void *z_save, void *hact, void *y, void *ws,
@@ -150,11 +153,11 @@ moe_status_t moe_combine_bwd(const moe_shape_t *shape, const void *d_out, const 
 
 /*
  * Expert FFN backward.
- *   d_h = d_y w2[e]^T ;  d_z = d_h * GeLU'(z_save) ;  d_w2[e] = hact^T d_y ;
+ *   d_h = d_y w2[e]^T ;  d_z = d_h * z_save  (z_save = GeLU'(z) from the forward) ;  d_w2[e] = hact^T d_y ;
  *   d_w1[e] = buf^T d_z ;  d_buf = d_z w1[e]^T          (rows r < kept[e] only)
  * d_w1, d_w2 are overwritten (one micro-batch), in `dtype` with fp32 accumulation; an expert
  * with kept[e] = 0 gets zero gradients.  Rows r >= kept[e] of d_buf are not written.
- * Uses E*C*f*sizeof(dtype) bytes of workspace for d_z.
+ * Uses E*C*f*sizeof(dtype) bytes of workspace for d_z, plus (bf16) the tile plans of the four GEMMs.
  */
 moe_status_t moe_expert_ffn_bwd(const moe_shape_t *shape, const void *d_y, const void *buf, const void *z_save,
                                 const void *hact, const void *w1, const void *w2, const int32_t *kept,

@@ -66,6 +66,11 @@ static double act_grad(double x, int act) {
 /* scalar access for the GeLU pins */
 double orc_act(double x, int act) { return act_fwd(x, act); }
 double orc_act_grad(double x, int act) { return act_grad(x, act); }
+/* the same derivative over an array (what a backward pass may keep instead of z) */
+void orc_act_grad_array(int64_t n, const double *z, double *g, int act) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) g[i] = act_grad(z[i], act);
+}
 
 /* Routing function, linear part: L[t,j] = sum_k X[t,k] Wg[k,j]. */
 void orc_gate_logits(int64_t T, int32_t h, int32_t E, const float *x, const float *wg, float *logits) {

@@ -45,6 +45,8 @@ def lib():
         L.orc_act.argtypes = [dbl, i32]
         L.orc_act_grad.restype = dbl
         L.orc_act_grad.argtypes = [dbl, i32]
+        L.orc_act_grad_array.restype = None
+        L.orc_act_grad_array.argtypes = [i64, p, p, i32]
         L.orc_gate_logits.argtypes = [i64, i32, i32, p, p, p]
         L.orc_top1_softmax.argtypes = [i64, i32, p, p, p, p]
         L.orc_route.argtypes = [i64, i32, i64, p, p, p, p, p]
@@ -83,6 +85,14 @@ def act(x: float, mode: int = ACT_GELU_ERF) -> float:
 
 def act_grad(x: float, mode: int = ACT_GELU_ERF) -> float:
     return lib().orc_act_grad(float(x), mode)
+
+
+def act_grad_array(z, mode: int = ACT_GELU_ERF):
+    """act'(z) element by element (float64)."""
+    z = np.ascontiguousarray(z, dtype=np.float64)
+    g = np.empty_like(z)
+    lib().orc_act_grad_array(z.size, z.ctypes.data, g.ctypes.data, mode)
+    return g
 
 
 def gate_logits(x, wg):

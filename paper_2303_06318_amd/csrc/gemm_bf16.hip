@@ -1,6 +1,6 @@
 // Grouped bf16 GEMM on gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation) for the
-// expert FFN: forward (Z = D W1 with fused GeLU, Y = H W2), data gradients (dH = dY W2^T with
-// fused GeLU', dD = dZ W1^T) and weight gradients (dW = A^T B over the kept rows).
+// expert FFN: forward (Z = D W1 with fused GeLU and GeLU', Y = H W2), data gradients (dH = dY W2^T
+// times the saved GeLU', dD = dZ W1^T) and weight gradients (dW = A^T B over the kept rows).
 //
 // One workgroup of 512 threads (8 waves, 2 x 4) owns a 256 x 256 output tile of one expert and
 // walks K in 32-deep tiles through four 32 KB LDS stages (three tiles, 96 KB, in flight).  Each
@@ -88,16 +88,22 @@ __device__ __forceinline__ float gelu_fast(float x, int act) {
     const float er = erf_exp_fast(fabsf(x) * 0.7071067811865476f, ex);
     return 0.5f * x * (1.0f + copysignf(er, x));
 }
-__device__ __forceinline__ float gelu_grad_fast(float x, int act) {
+// GeLU and its derivative together (they share the erf / tanh and the exponential).
+__device__ __forceinline__ void gelu_both_fast(float x, int act, float &h, float &g) {
     if (act == MOE_GELU_TANH) {
         const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
         const float th = tanh_fast(u);
         const float du = 0.7978845608028654f * (1.0f + 0.134145f * x * x);
-        return 0.5f * (1.0f + th) + 0.5f * x * (1.0f - th * th) * du;
+        const float phi = 0.5f * (1.0f + th);
+        h = x * phi;
+        g = phi + 0.5f * x * (1.0f - th * th) * du;
+        return;
     }
     float ex;
     const float er = erf_exp_fast(fabsf(x) * 0.7071067811865476f, ex);
-    return 0.5f * (1.0f + copysignf(er, x)) + x * ex * 0.3989422804014327f;
+    const float phi = 0.5f * (1.0f + copysignf(er, x));
+    h = x * phi;
+    g = phi + x * ex * 0.3989422804014327f;
 }
 
 // Buffer resource (raw, stride 0) over one expert's operand: lanes whose byte offset is not below
@@ -649,16 +655,71 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
         for_each_quad([&](bf16_t *pos, const f32x4 &v) { put4(pos, v); });
         flush(C);
     } else if (EPI == EPI_GELU) {
-        if (d.C2) {
-            for_each_quad([&](bf16_t *pos, const f32x4 &v) { put4(pos, v); });
-            flush((bf16_t *)d.C2 + (int64_t)e * d.strideC);
-            __syncthreads();
-        }
-        for_each_quad([&](bf16_t *pos, const f32x4 &v) {
-            f32x4 g = {gelu_fast(v[0], act), gelu_fast(v[1], act), gelu_fast(v[2], act), gelu_fast(v[3], act)};
-            put4(pos, g);
-        });
-        flush(C);
+        // The activation is a compile-time constant inside (one branch per tile, not per element).
+        auto gelu_stage = [&](auto actc) __attribute__((always_inline)) {
+            constexpr int ACT = decltype(actc)::value;
+            if (d.C2) {
+                // Second output act'(z), which is all the backward pass needs of z.  Both values are
+                // computed in one go and staged side by side, so the tile goes out in three parts of
+                // at most 128 rows (two staging areas of 128 rows fit the LDS): the wave's block rows
+                // 0-1, its block rows 2-3, and the ninth block row of a tall tile.
+                bf16_t *stG = st, *stH = st + 128 * CLD;
+                bf16_t *outG = (bf16_t *)d.C2 + (int64_t)e * d.strideC;
+                auto both16 = [&](const f32x16 &a, int srow, int col) __attribute__((always_inline)) {
+#pragma unroll
+                    for (int vq = 0; vq < 4; ++vq) {
+                        f32x4 g, hv;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            float h1, g1;
+                            gelu_both_fast(a[vq * 4 + q], ACT, h1, g1);
+                            hv[q] = h1;
+                            g[q] = g1;
+                        }
+                        const int off = srow * CLD + col + vq * 8 + (lane >> 5) * 4;
+                        put4(stG + off, g);
+                        put4(stH + off, hv);
+                    }
+                };
+                // staged row sr of part `part` is tile row trow(sr)
+                auto flush_part = [&](int part, int nrows) __attribute__((always_inline)) {
+                    __syncthreads();
+                    for (int p = 0; p < nrows / 16; ++p) {
+                        const int sr = (tid >> 5) + 16 * p;
+                        const int trow = part == 2 ? 256 + sr : (sr >> 6) * 128 + part * 64 + (sr & 63);
+                        const int gm = m0 + trow, gn = n0 + (tid & 31) * 8;
+                        const u32x4 vg = *(const u32x4 *)(stG + sr * CLD + (tid & 31) * 8);
+                        const u32x4 vh = *(const u32x4 *)(stH + sr * CLD + (tid & 31) * 8);
+                        if (gm < mlim && gn < d.N) {
+                            *(u32x4 *)(outG + (int64_t)gm * d.ldc + gn) = vg;
+                            *(u32x4 *)(C + (int64_t)gm * d.ldc + gn) = vh;
+                        }
+                    }
+                    __syncthreads();
+                };
+#pragma unroll
+                for (int part = 0; part < 2; ++part) {
+#pragma unroll
+                    for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+                            both16(acc[2 * part + ii][j], (wm >> 7) * 64 + ii * 32 + (lane & 31), wn + j * 32);
+                    flush_part(part, 128);
+                }
+                if (tall) {
+                    both16(accx, lane & 31, wn + jx * 32);
+                    flush_part(2, 32);
+                }
+            } else {
+                for_each_quad([&](bf16_t *pos, const f32x4 &v) {
+                    f32x4 g = {gelu_fast(v[0], ACT), gelu_fast(v[1], ACT), gelu_fast(v[2], ACT), gelu_fast(v[3], ACT)};
+                    put4(pos, g);
+                });
+            }
+        };
+        if (act == MOE_GELU_TANH) gelu_stage(std::integral_constant<int, MOE_GELU_TANH>{});
+        else gelu_stage(std::integral_constant<int, MOE_GELU_ERF>{});
+        if (!d.C2) flush(C);
     } else {
         const bf16_t *Zin = (const bf16_t *)d.Zin + (int64_t)e * d.strideC;
         auto zpass = [&](int p) {
@@ -671,10 +732,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
         for (int p = 0; p < 16; ++p) zpass(p);
         if (tall) { zpass(16); zpass(17); }
         __syncthreads();
-        for_each_quad([&](bf16_t *pos, const f32x4 &v) {
+        for_each_quad([&](bf16_t *pos, const f32x4 &v) {     // Zin holds act'(z)
             const bf16x4 z = *(const bf16x4 *)pos;
-            f32x4 g = {v[0] * gelu_grad_fast((float)z[0], act), v[1] * gelu_grad_fast((float)z[1], act),
-                       v[2] * gelu_grad_fast((float)z[2], act), v[3] * gelu_grad_fast((float)z[3], act)};
+            f32x4 g = {v[0] * (float)z[0], v[1] * (float)z[1], v[2] * (float)z[2], v[3] * (float)z[3]};
             put4(pos, g);
         });
         flush(C);

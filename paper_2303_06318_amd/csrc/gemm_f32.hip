@@ -69,11 +69,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmDesc d) {
             int64_t o = (int64_t)gm * d.ldc + gn;
             float v = acc[i][j];
             if (EPI == EPI_GELU) {
-                if (d.C2) ((float *)d.C2 + (int64_t)e * d.strideC)[o] = v;
+                if (d.C2) ((float *)d.C2 + (int64_t)e * d.strideC)[o] = act_grad(v, d.act);
                 C[o] = act_fwd(v, d.act);
             } else if (EPI == EPI_DGELU) {
-                float z = ((const float *)d.Zin + (int64_t)e * d.strideC)[o];
-                C[o] = v * act_grad(z, d.act);
+                C[o] = v * ((const float *)d.Zin + (int64_t)e * d.strideC)[o];
             } else {
                 C[o] = v;
             }

@@ -49,8 +49,8 @@ enum { EPI_STORE = 0, EPI_GELU = 1, EPI_DGELU = 2 };
 struct GemmDesc {
     const void *A, *B;
     void *C;          // main output
-    void *C2;         // EPI_GELU: optional pre-activation output (may be null)
-    const void *Zin;  // EPI_DGELU: pre-activation input
+    void *C2;         // EPI_GELU: optional second output act'(pre-activation) (may be null)
+    const void *Zin;  // EPI_DGELU: act'(pre-activation) as saved by EPI_GELU; the result is multiplied by it
     const int32_t *kept;
     int64_t strideA, strideB, strideC;   // elements between experts
     int32_t M, N, K;                     // upper bounds / fixed sizes

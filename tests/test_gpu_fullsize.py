@@ -94,7 +94,7 @@ def test_full_size(orc, name):
         assert relfro(d_y_g[e, rs], dY) <= t
         dp = (inp.d_out[toks].astype(np.float64) * Y).sum(1)
         assert relfro(dp_g[toks], dp) <= t
-        assert relfro(z_g[e, rs], Z) <= t
+        assert relfro(z_g[e, rs], orc.act_grad_array(Z)) <= t     # z_save holds GeLU'(z)
         dD, _, _, _ = orc.ffn_bwd(dY, D[e, rs], Z, H, inp.w1[e], inp.w2[e])
         assert relfro(d_buf_g[e, rs], dD) <= t, (e, "d_buf")
     # weight gradients: a few columns of f for two experts, over all kept rows

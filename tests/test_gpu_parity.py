@@ -107,7 +107,7 @@ def test_backward_parity(orc, name, act):
     d_y, d_buf = host(layer.d_y), host(layer.d_buf)
     for ex in range(wl.E):
         k = int(kept[ex])
-        assert relfro(z[ex, :k], fw["Z"][ex, :k]) <= t
+        assert relfro(z[ex, :k], orc.act_grad_array(fw["Z"][ex, :k], act)) <= t       # z_save holds act'(z)
         assert relfro(d_buf[ex, :k], bw["dD"][ex, :k]) <= t
     assert relfro(d_y, bw["dY"]) <= t           # all rows: empty slots are defined as zero
     assert relfro(host(layer.d_gate_p), bw["dp"]) <= t
