@@ -248,30 +248,58 @@ __global__ __launch_bounds__(256) void gate_dx_kernel(const float *w_gate, const
         __syncthreads();
         const int nt = (int)(t_end - tb < TT ? t_end - tb : TT);
         if (!kin) continue;
-        // groups of 4 tokens: issue the 4 row loads, then the arithmetic, then the 4 stores
+        // groups of 4 tokens: the row loads of the next group are issued before the arithmetic of
+        // this one (the kernel runs 2 waves per SIMD, so the loads in flight per wave decide the
+        // bandwidth), then the 4 stores
+        auto load_row = [&](int tt, float(&v)[CW]) {
+            bool zero = tt >= nt;
+            const bf16_t *src = d_x + (tb + (zero ? 0 : tt)) * h + k0;
+            if (d_buf && !zero) {
+                const int r = srow[tt];
+                zero = r < 0;
+                src = d_buf + (int64_t)(zero ? 0 : r) * h + k0;
+            }
+            if (zero) {
+#pragma unroll
+                for (int c = 0; c < CW; ++c) v[c] = 0.f;
+            } else {
+#pragma unroll
+                for (int c = 0; c < CW; ++c) v[c] = (float)src[c];
+            }
+        };
+        auto load_row8 = [&](int tt) {           // CW == 8: the raw 16 bytes, zero for a dropped token
+            bool zero = tt >= nt;
+            const bf16_t *src = d_x + (tb + (zero ? 0 : tt)) * h + k0;
+            if (d_buf && !zero) {
+                const int r = srow[tt];
+                zero = r < 0;
+                src = d_buf + (int64_t)(zero ? 0 : r) * h + k0;
+            }
+            u32x4 raw = {0u, 0u, 0u, 0u};
+            if (!zero) raw = *(const u32x4 *)src;
+            return raw;
+        };
+        u32x4 nxt[4];
+        if (CW == 8) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) nxt[u] = load_row8(u);
+        }
         for (int t4 = 0; t4 < nt; t4 += 4) {
             float v[4][CW];
+            if (CW == 8) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int tt = t4 + u;
-                bool zero = tt >= nt;
-                const bf16_t *src = d_x + (tb + (zero ? 0 : tt)) * h + k0;
-                if (d_buf && !zero) {
-                    const int r = srow[tt];
-                    zero = r < 0;
-                    src = d_buf + (int64_t)(zero ? 0 : r) * h + k0;
+                for (int u = 0; u < 4; ++u) {
+                    const bf16x8 b = __builtin_bit_cast(bf16x8, nxt[u]);
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) v[u][c < CW ? c : 0] = (float)b[c];
                 }
-                if (zero) {
+                if (t4 + 4 < nt) {
 #pragma unroll
-                    for (int c = 0; c < CW; ++c) v[u][c] = 0.f;
-                } else if (CW == 8) {
-                    const bf16x8 b = *(const bf16x8 *)src;
-#pragma unroll
-                    for (int c = 0; c < 8; ++c) v[u][c] = (float)b[c];
-                } else {
-#pragma unroll
-                    for (int c = 0; c < CW; ++c) v[u][c] = (float)src[c];
+                    for (int u = 0; u < 4; ++u) nxt[u] = load_row8(t4 + 4 + u);
                 }
+            } else {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) load_row(t4 + u, v[u]);
             }
 #pragma unroll
             for (int j = 0; j < EJ; ++j) {
@@ -290,7 +318,7 @@ __global__ __launch_bounds__(256) void gate_dx_kernel(const float *w_gate, const
                 if (CW == 8) {
                     bf16x8 b;
 #pragma unroll
-                    for (int c = 0; c < 8; ++c) b[c] = (bf16_t)v[u][c];
+                    for (int c = 0; c < 8; ++c) b[c] = (bf16_t)v[u][c < CW ? c : 0];
                     *(bf16x8 *)row = b;
                 } else {
 #pragma unroll
