@@ -26,7 +26,12 @@
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
  *    only enqueue work on it; there is no host synchronisation and no host read
  *    of device data (kept_e is read on the device, so launches cover C rows per
- *    expert and skip the unused part).
+ *    expert and skip the unused part).  One exception to "only on `stream`":
+ *    moe_expert_ffn_bwd (bf16) runs its two weight-gradient GEMMs on an internal
+ *    stream, created once per device on first use and kept until the process ends;
+ *    that stream starts behind an event of `stream` and `stream` waits for its last
+ *    event before the call's work is complete, so the caller still orders everything
+ *    on `stream` alone.
  *  - `dtype` is the storage type of x, buffers, expert weights and their
  *    gradients: MOE_BF16 (fp32 accumulation on MFMA) or MOE_F32.  The gate
  *    (w_gate, logits, probs, gate_p and their gradients) is always fp32.

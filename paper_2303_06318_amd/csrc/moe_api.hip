@@ -3,6 +3,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <mutex>
 #include "moe_common.h"
 
 namespace moe {
@@ -163,6 +164,35 @@ static size_t ws_bytes_checked(const moe_shape_t *sh, int for_backward) {
     if (ffn_bwd_ws_bytes(sh) > need) need = ffn_bwd_ws_bytes(sh);
     if (round256(gate_bwd_ws_bytes(sh)) > need) need = round256(gate_bwd_ws_bytes(sh));
     return need;
+}
+
+// Side stream of the FFN backward (bf16): the two weight-gradient GEMMs do not depend on the data-gradient
+// GEMM that runs next to them, and every GEMM launch ends with compute units idling while the last tiles
+// finish; on a second stream the other GEMM's workgroups move into those units as they free up.  One
+// stream and three events per device, created on first use and kept until the process ends; the side
+// stream starts behind an event of the caller's stream and the caller's stream waits for its last event,
+// so for the caller the call is still ordered on `stream` alone.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, mid = nullptr, join = nullptr;
+    bool ok = false, tried = false;
+};
+static SideStream *side_stream() {
+    static SideStream per_device[16];
+    static std::mutex mu;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
+    SideStream &ss = per_device[dev];
+    if (!ss.tried) {
+        ss.tried = true;
+        ss.ok = hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) == hipSuccess &&
+                hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming) == hipSuccess &&
+                hipEventCreateWithFlags(&ss.mid, hipEventDisableTiming) == hipSuccess &&
+                hipEventCreateWithFlags(&ss.join, hipEventDisableTiming) == hipSuccess;
+        if (!ss.ok) (void)hipGetLastError();
+    }
+    return ss.ok ? &ss : nullptr;
 }
 
 static moe_status_t check_ws(const char *fn, const void *ws, size_t have, size_t need) {
@@ -331,9 +361,30 @@ moe_status_t moe_expert_ffn_bwd(const moe_shape_t *shape, const void *d_y, const
         for (int i = 0; i < 4; ++i) { g[i].plan = pl; pl += gemm_bf16_plan_bytes(g[i]); }
         if ((st = launch_gemm_bf16_plans(g, 4, hs)) != MOE_OK) return st;
     }
-    for (int i = 0; i < 4; ++i)
-        if ((st = bf ? launch_gemm_bf16(g[i], hs) : launch_gemm_f32(g[i], hs)) != MOE_OK) return st;
-    return MOE_OK;
+    SideStream *ss = bf ? side_stream() : nullptr;
+    if (ss == nullptr) {     // fp32, or no side stream: one after the other
+        for (int i = 0; i < 4; ++i)
+            if ((st = bf ? launch_gemm_bf16(g[i], hs) : launch_gemm_f32(g[i], hs)) != MOE_OK) return st;
+        return MOE_OK;
+    }
+    // caller's stream: plans, dH, dD;  side stream: dW2 (next to dH), dW1 (needs d_z, next to dD)
+    auto hip_ok = [](hipError_t e, const char *what) {
+        if (e == hipSuccess) return MOE_OK;
+        set_error("moe_expert_ffn_bwd: %s: %s", what, hipGetErrorString(e));
+        return MOE_ERR_HIP;
+    };
+    if ((st = hip_ok(hipEventRecord(ss->fork, hs), "event record")) != MOE_OK) return st;
+    if ((st = hip_ok(hipStreamWaitEvent(ss->stream, ss->fork, 0), "stream wait")) != MOE_OK) return st;
+    if ((st = launch_gemm_bf16(g[0], hs)) != MOE_OK) return st;
+    moe_status_t side = launch_gemm_bf16(g[1], ss->stream);
+    if (side == MOE_OK) side = hip_ok(hipEventRecord(ss->mid, hs), "event record");
+    if (side == MOE_OK) side = hip_ok(hipStreamWaitEvent(ss->stream, ss->mid, 0), "stream wait");
+    if (side == MOE_OK) side = launch_gemm_bf16(g[2], ss->stream);
+    // whatever happened on the side stream, the caller's stream waits for what was enqueued there
+    st = launch_gemm_bf16(g[3], hs);
+    moe_status_t j = hip_ok(hipEventRecord(ss->join, ss->stream), "event record");
+    if (j == MOE_OK) j = hip_ok(hipStreamWaitEvent(hs, ss->join, 0), "stream wait");
+    return side != MOE_OK ? side : (st != MOE_OK ? st : j);
 }
 
 moe_status_t moe_dispatch_bwd(const moe_shape_t *shape, const void *d_buf, const int32_t *expert, const int32_t *slot,
