@@ -317,9 +317,19 @@ __global__ __launch_bounds__(PLAN_THREADS) void gemm_plan_kernel(PlanArgs args) 
             ent = make_int4(e | (s_nb[e] << 8) | (1 << 12), r, 0, s_kept[e]);
             pos = s_ts[x + 1] + s_sl[x] + (q - s_sl[x]);
         } else {
-            const int mts = s_hv[e], nti = r / mts, mti = r - nti * mts;   // m fastest
+            const int mts = s_hv[e];
             // the first nb % mts tiles of a column hold one block more than the others
             const int bb = s_nb[e] / mts, bx = s_nb[e] - bb * mts;
+            int nti = r / mts, mti = r - nti * mts;                        // m fastest
+            if (bx == 0 && mts > 4) {
+                // many equal m-tiles (the weight gradients): n fastest inside groups of 8 n-tiles, so that
+                // the 32 tiles an XCD works on together are 4 m-tiles x 8 n-tiles (12 operand panels)
+                // rather than 16 x 2 (18 panels)
+                const int ng = r / (mts * 8), rr = r - ng * (mts * 8);
+                const int gw = nt - ng * 8 < 8 ? nt - ng * 8 : 8;
+                mti = rr / gw;
+                nti = ng * 8 + (rr - mti * gw);
+            }
             const int nblk = bb + (mti < bx ? 1 : 0), blk0 = mti * bb + (mti < bx ? mti : bx);
             ent = make_int4(e | (nblk << 8), nti, blk0, s_kept[e]);
             pos = s_ts[x] + s_sl[x] + (q - s_ts[x]);
