@@ -3,6 +3,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <mutex>
 #include "moe_common.h"
 
@@ -186,6 +187,10 @@ static SideStream *side_stream() {
     SideStream &ss = per_device[dev];
     if (!ss.tried) {
         ss.tried = true;
+        // MOE_TED_SERIAL=1 keeps everything on the caller's stream (per-kernel durations in a profile then
+        // are those of kernels that had the chip to themselves)
+        const char *serial = getenv("MOE_TED_SERIAL");
+        if (serial != nullptr && serial[0] == '1') return nullptr;
         ss.ok = hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) == hipSuccess &&
                 hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming) == hipSuccess &&
                 hipEventCreateWithFlags(&ss.mid, hipEventDisableTiming) == hipSuccess &&
