@@ -329,6 +329,142 @@ __global__ __launch_bounds__(256) void gate_dx_kernel(const float *w_gate, const
     }
 }
 
+// The same sum on the matrix cores, for E <= 64:  d_x[t, c0 .. c0+255] for tiles of 32 tokens.
+// The rank-E product dL Wg^T is one v_mfma_f32_32x32x16_bf16 per 32 x 32 block, 16 experts and term;
+// both factors are split in two bf16 pieces and the three leading products are summed in fp32
+// (error about 2^-16 of the term, far below the bf16 rounding of d_x).  Each of the 4 waves owns 64
+// columns and keeps its Wg^T fragments in registers; the 32 x 256 fp32 result goes through LDS so
+// that the streaming part (gathered row in, sum out) moves 16 contiguous bytes per lane.  A
+// workgroup walks up to 8 token tiles; the token rows and the d_logits rows of the next tile are
+// requested before the arithmetic of the current one.
+template <int KB>       // 16-expert blocks: E <= 16 KB
+__global__ __launch_bounds__(256) void gate_dx_mfma_kernel(const float *w_gate, const float *d_logits, bf16_t *d_x,
+                                                            int64_t T, int h, int E, int tiles_per_wg,
+                                                            const bf16_t *d_buf, const int32_t *expert,
+                                                            const int32_t *slot, int64_t C) {
+    constexpr int TT = 32, GLD = 256 + 4;
+    __shared__ __attribute__((aligned(16))) float G[TT][GLD];
+    __shared__ int32_t srow[256];                   // buffer row of each of the workgroup's tokens, -1 if dropped
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c0 = blockIdx.x * 256;
+    // B fragments: lane holds Wg[col][16 kb + 8 (lane / 32) .. + 7], col = c0 + 64 wave + 32 j + lane % 32,
+    // in two bf16 pieces (zeros outside the matrix)
+    bf16x8 bh[2][KB], bl[2][KB];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int col = c0 + wave * 64 + j * 32 + (lane & 31);
+        const float *row = w_gate + (int64_t)(col < h ? col : 0) * E;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int k = kb * 16 + 8 * (lane >> 5) + q;
+                const float v = (col < h && k < E) ? row[k] : 0.f;
+                const bf16_t hq = f32_to_bf16(v);
+                bh[j][kb][q] = hq;
+                bl[j][kb][q] = f32_to_bf16(v - bf16_to_f32(hq));
+            }
+    }
+    const int c8 = (tid & 31) * 8;                  // streaming part: 8 columns of one token row
+    const bool cin = c0 + c8 < h;
+    const int64_t t_first = (int64_t)blockIdx.y * tiles_per_wg * TT;
+    // raw d_logits values of the lane's A fragments, loaded one tile ahead
+    float araw[KB][8];
+    auto load_a = [&](int64_t tb) {
+        const int64_t trow = tb + (lane & 31);
+        const float *row = d_logits + (trow < T ? trow : 0) * E;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int k = kb * 16 + 8 * (lane >> 5) + q;
+                araw[kb][q] = (trow < T && k < E) ? row[k] : 0.f;
+            }
+    };
+    load_a(t_first);
+    if (d_buf) {                                    // tiles_per_wg * 32 <= 256 tokens: one per thread, all tiles at once
+        int32_t r = -1;
+        if (tid < tiles_per_wg * TT && t_first + tid < T) {
+            const int sl = slot[t_first + tid];
+            if (sl >= 0) r = (int32_t)((int64_t)expert[t_first + tid] * C + sl);
+        }
+        srow[tid] = r;
+    }
+    __syncthreads();
+    // the 4 token rows of a thread (16 bytes each), requested one tile ahead
+    u32x4 raw[4], nxt[4];
+    auto load_rows = [&](int it, u32x4(&dst)[4]) {
+        const int64_t tb = t_first + (int64_t)it * TT;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int tt = (tid >> 5) + 8 * u;
+            dst[u] = u32x4{0u, 0u, 0u, 0u};
+            if (cin && it < tiles_per_wg && tb + tt < T) {
+                if (d_buf) {
+                    const int r = srow[it * TT + tt];
+                    if (r >= 0) dst[u] = *(const u32x4 *)(d_buf + (int64_t)r * h + c0 + c8);
+                } else {
+                    dst[u] = *(const u32x4 *)(d_x + (tb + tt) * h + c0 + c8);
+                }
+            }
+        }
+    };
+    load_rows(0, nxt);
+    for (int it = 0; it < tiles_per_wg; ++it) {
+        const int64_t tb = t_first + (int64_t)it * TT;
+        if (tb >= T) break;
+        if (it > 0) __syncthreads();                // G of the previous tile has been read
+#pragma unroll
+        for (int u = 0; u < 4; ++u) raw[u] = nxt[u];
+        load_rows(it + 1, nxt);
+        f32x16 acc[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            bf16x8 ah, al;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const bf16_t hq = f32_to_bf16(araw[kb][q]);
+                ah[q] = hq;
+                al[q] = f32_to_bf16(araw[kb][q] - bf16_to_f32(hq));
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                // operands swapped: the lane ends up with token row lane % 32 and 4 consecutive columns per quad
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh[j][kb], ah, acc[j], 0, 0, 0);
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bl[j][kb], ah, acc[j], 0, 0, 0);
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh[j][kb], al, acc[j], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const f32x4 v = {acc[j][vq * 4], acc[j][vq * 4 + 1], acc[j][vq * 4 + 2], acc[j][vq * 4 + 3]};
+                *(f32x4 *)&G[lane & 31][wave * 64 + j * 32 + vq * 8 + (lane >> 5) * 4] = v;
+            }
+        if (it + 1 < tiles_per_wg && tb + TT < T) load_a(tb + TT);
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int tt = (tid >> 5) + 8 * u;
+            if (!cin || tb + tt >= T) continue;
+            const f32x4 g0 = *(const f32x4 *)&G[tt][c8], g1 = *(const f32x4 *)&G[tt][c8 + 4];
+            const bf16x8 b = __builtin_bit_cast(bf16x8, raw[u]);
+            bf16x8 o;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                o[q] = f32_to_bf16(bf16_to_f32(b[q]) + g0[q]);
+                o[q + 4] = f32_to_bf16(bf16_to_f32(b[q + 4]) + g1[q]);
+            }
+            *(bf16x8 *)(d_x + (tb + tt) * h + c0 + c8) = o;
+        }
+    }
+}
+
 // ------------------------------------------------------------------ host side
 static int simple_chunks(const moe_shape_t *sh) {
     int64_t n = (sh->T + 1023) / 1024;
@@ -402,6 +538,19 @@ static void launch_dx(const moe_shape_t *sh, const float *w_gate, const float *d
                        sh->E, j0, chunk_len, (const bf16_t *)d_buf, expert, slot, sh->C);
 }
 
+static void launch_dx_mfma(const moe_shape_t *sh, const float *w_gate, const float *d_logits, void *d_x, hipStream_t s,
+                           const void *d_buf = nullptr, const int32_t *expert = nullptr, const int32_t *slot = nullptr) {
+    const int tiles_per_wg = 8;                     // at most 8: the kernel keeps one gather row per thread
+    dim3 grid((unsigned)((sh->h + 255) / 256), (unsigned)((sh->T + 32 * tiles_per_wg - 1) / (32 * tiles_per_wg)));
+#define MOE_DX_MFMA(KB)                                                                                                  \
+    hipLaunchKernelGGL((gate_dx_mfma_kernel<KB>), grid, dim3(256), 0, s, w_gate, d_logits, (bf16_t *)d_x, sh->T, sh->h, \
+                       sh->E, tiles_per_wg, (const bf16_t *)d_buf, expert, slot, sh->C)
+    if (sh->E <= 16) MOE_DX_MFMA(1);
+    else if (sh->E <= 32) MOE_DX_MFMA(2);
+    else MOE_DX_MFMA(4);
+#undef MOE_DX_MFMA
+}
+
 moe_status_t run_gate_bwd(const moe_shape_t *sh, const float *d_gate_p, const float *probs, const int32_t *expert,
                           const void *x, const float *w_gate, float *d_logits, float *d_w_gate, void *d_x_accum,
                           void *ws, hipStream_t s) {
@@ -441,8 +590,7 @@ moe_status_t run_gate_bwd(const moe_shape_t *sh, const float *d_gate_p, const fl
                            d_w_gate, sh->h, E, Epad, nch);
     }
     if (d_x_accum) {
-        if (E <= 16) launch_dx<8, 16>(sh, w_gate, d_logits, d_x_accum, 0, s);
-        else if (E <= 32) launch_dx<4, 32>(sh, w_gate, d_logits, d_x_accum, 0, s);
+        if (E <= 64) launch_dx_mfma(sh, w_gate, d_logits, d_x_accum, s);
         else
             for (int j0 = 0; j0 < E; j0 += 64) launch_dx<2, 64>(sh, w_gate, d_logits, d_x_accum, j0, s);
     }
@@ -474,8 +622,7 @@ moe_status_t run_dispatch_bwd_fused(const moe_shape_t *sh, const void *d_buf, co
                                     const int32_t *slot, void *d_x, const float *d_logits, const float *w_gate,
                                     hipStream_t s) {
     const int E = sh->E;
-    if (E <= 16) launch_dx<8, 16>(sh, w_gate, d_logits, d_x, 0, s, d_buf, expert, slot);
-    else if (E <= 32) launch_dx<4, 32>(sh, w_gate, d_logits, d_x, 0, s, d_buf, expert, slot);
+    if (E <= 64) launch_dx_mfma(sh, w_gate, d_logits, d_x, s, d_buf, expert, slot);
     else {
         launch_dx<2, 64>(sh, w_gate, d_logits, d_x, 0, s, d_buf, expert, slot);
         for (int j0 = 64; j0 < E; j0 += 64) launch_dx<2, 64>(sh, w_gate, d_logits, d_x, j0, s);

@@ -214,6 +214,7 @@ struct FragAddr {
 constexpr int PLAN_HDR_INTS = 32;
 constexpr int PLAN_THREADS = 1024;
 constexpr int MAX_PLANS = 4;
+constexpr int PLAN_SLICES = 8;                 // blocks per plan: each recomputes the header and fills a slice of the tiles
 
 // Measured cost of a heavy tile by its block count, in half blocks of a full tile's main loop:
 // up to 6 blocks run through the loop that skips blocks (slower per block), 7 and 8 through the
@@ -295,10 +296,12 @@ __global__ __launch_bounds__(PLAN_THREADS) void gemm_plan_kernel(PlanArgs args) 
         s_sl[tid] = (int)(((long long)tid * nL) >> 3);
     }
     __syncthreads();
-    if (tid < 8) p.plan[tid] = 0;
-    if (tid <= 8) p.plan[8 + tid] = s_ts[tid] + s_sl[tid];
+    if (blockIdx.y == 0) {
+        if (tid < 8) p.plan[tid] = 0;
+        if (tid <= 8) p.plan[8 + tid] = s_ts[tid] + s_sl[tid];
+    }
     int4 *tiles = (int4 *)(p.plan + PLAN_HDR_INTS);
-    for (int t = tid; t < nH + nL; t += PLAN_THREADS) {
+    for (int t = blockIdx.y * PLAN_THREADS + tid; t < nH + nL; t += PLAN_THREADS * PLAN_SLICES) {
         const bool light = t >= nH;
         const int q = light ? t - nH : t;
         const int *pre = light ? s_preL : s_preH;
@@ -798,7 +801,7 @@ moe_status_t launch_gemm_bf16_plans(const GemmDesc *descs, int n, hipStream_t s)
         p.rows_from_kept = d.rows_from_kept; p.maxb = d.a_xc ? 8 : MAXB;
         p.cus_per_xcd = num_compute_units() / 8 > 0 ? num_compute_units() / 8 : 1;
     }
-    hipLaunchKernelGGL(gemm_plan_kernel, dim3(n), dim3(PLAN_THREADS), 0, s, args);
+    hipLaunchKernelGGL(gemm_plan_kernel, dim3(n, PLAN_SLICES), dim3(PLAN_THREADS), 0, s, args);
     return check_launch("gemm_plan");
 }
 
