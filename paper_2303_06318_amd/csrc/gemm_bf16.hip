@@ -234,7 +234,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void gemm_plan_kernel(PlanArgs args) 
     const PlanDesc &p = args.p[blockIdx.x];
     __shared__ int s_kept[256], s_nb[256], s_hv[256], s_nk[256];
     __shared__ int s_preH[257], s_preL[257];      // tiles of the experts before e (heavy, light)
-    __shared__ long long s_preW[257];             // work of the heavy tiles of the experts before e
+    __shared__ long long s_preW[257], s_w[256];   // work of the heavy tiles of the experts before e, and of expert e
     __shared__ int s_ts[9], s_sl[9];              // split points of the heavy and of the light list
     const int tid = threadIdx.x, nt = p.nt;
     if (tid < p.E) {
@@ -245,22 +245,30 @@ __global__ __launch_bounds__(PLAN_THREADS) void gemm_plan_kernel(PlanArgs args) 
         s_kept[tid] = kx;
         s_nb[tid] = nb;
         s_hv[tid] = nb > LIGHT_BLOCKS ? (nb + p.maxb - 1) / p.maxb : 0;
-        s_nk[tid] = nk > 0 ? nk : 1;              // never 0: every heavy tile must fall into some share
+        const int nkf = nk > 0 ? nk : 1;          // never 0: every heavy tile must fall into some share
+        s_nk[tid] = nkf;
+        long long w = 0;
+        if (nb > LIGHT_BLOCKS) {  // one column of the expert's tiles: bx tiles of bb + 1 blocks, the others of bb
+            const int hv = (nb + p.maxb - 1) / p.maxb, bb = nb / hv, bx = nb - bb * hv;
+            w = (long long)(bx * tile_cost(bb + 1) + (hv - bx) * tile_cost(bb)) * nkf * nt;
+        }
+        s_w[tid] = w;
     }
     __syncthreads();
-    if (tid == 0) {
+    if (tid < p.E) {              // exclusive prefix sums, every thread for itself (E <= 256: no dependent chain)
         int h = 0, l = 0;
         long long w = 0;
-        for (int e = 0; e < p.E; ++e) {
-            s_preH[e] = h; s_preL[e] = l; s_preW[e] = w;
+        for (int e = 0; e < tid; ++e) {
             h += s_hv[e] * nt;
             l += (s_nb[e] > 0 && s_nb[e] <= LIGHT_BLOCKS) ? nt : 0;
-            if (s_hv[e]) {       // one column of the expert's tiles: bx tiles of bb + 1 blocks, the others of bb
-                const int bb = s_nb[e] / s_hv[e], bx = s_nb[e] - bb * s_hv[e];
-                w += (long long)(bx * tile_cost(bb + 1) + (s_hv[e] - bx) * tile_cost(bb)) * s_nk[e] * nt;
-            }
+            w += s_w[e];
         }
-        s_preH[p.E] = h; s_preL[p.E] = l; s_preW[p.E] = w;
+        s_preH[tid] = h; s_preL[tid] = l; s_preW[tid] = w;
+        if (tid == p.E - 1) {
+            s_preH[p.E] = h + s_hv[tid] * nt;
+            s_preL[p.E] = l + ((s_nb[tid] > 0 && s_nb[tid] <= LIGHT_BLOCKS) ? nt : 0);
+            s_preW[p.E] = w + s_w[tid];
+        }
     }
     __syncthreads();
     const int nH = s_preH[p.E], nL = s_preL[p.E];
