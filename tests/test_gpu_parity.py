@@ -231,3 +231,45 @@ def test_backward_unfused_order(orc, name):
     assert relfro(host(layer.d_x), bw["dX"]) <= t
     assert relfro(host(layer.d_w_gate), bw["dWg"]) <= t
     assert relfro(host(layer.d_logits), bw["dL"]) <= t
+
+
+def _random_shapes():
+    """Seeded shapes whose per-expert row counts hit every kind of GEMM tile: experts without rows, light
+    tiles (up to 4 blocks of 32 rows), tiles of 5 to 9 blocks, several m-tiles per expert, ragged h and f."""
+    rng = np.random.default_rng(20260)
+    out = []
+    for i in range(10):
+        E = int(rng.choice([1, 2, 3, 5, 8, 13, 24, 40]))
+        per = int(rng.choice([20, 90, 150, 200, 270, 300, 520, 600]))
+        T = max(1, E * per + int(rng.integers(-15, 16)))
+        cf = float(rng.choice([0.6, 1.0, 1.4]))
+        h = 8 * int(rng.integers(3, 40))
+        f = 8 * int(rng.integers(3, 40))
+        out.append(synth.scaled(W["cfg4_skewed_fwd" if i % 2 else "cfg5_6p7b_tp4_fwdbwd"], T=T, h=h, f=f, E=E,
+                                capacity_factor=cf, backward=True, seed=100 + i, name="random%d" % i))
+    return out
+
+
+@pytest.mark.parametrize("wl", _random_shapes(), ids=lambda w: "%s_T%d_E%d_h%d_f%d" % (w.name, w.T, w.E, w.h, w.f))
+def test_random_shapes(orc, wl):
+    inp, dev, layer = run_forward(wl, backward=True)
+    layer.backward(dev.d_out, dev.x, dev.wg, dev.w1, dev.w2)
+    torch.cuda.synchronize()
+    g_logits = host(layer.logits)
+    e, slot, kept = check_routing(orc, layer, wl, g_logits)
+    fw = orc.layer_forward(inp.x, inp.wg, inp.w1, inp.w2, wl.C, logits=g_logits)
+    bw = orc.layer_backward(fw, inp.d_out, inp.x, inp.wg, inp.w1, inp.w2)
+    t = tol(wl)
+    hact, y, d_buf = host(layer.hact), host(layer.y), host(layer.d_buf)
+    for ex in range(wl.E):
+        k = int(kept[ex])
+        if k == 0:
+            continue
+        assert relfro(hact[ex, :k], fw["H"][ex, :k]) <= t, ex
+        assert relfro(y[ex, :k], fw["Y"][ex, :k]) <= t, ex
+        assert relfro(d_buf[ex, :k], bw["dD"][ex, :k]) <= t, ex
+    assert relfro(host(layer.out), fw["out"]) <= t
+    assert relfro(host(layer.d_w1), bw["dW1"]) <= t
+    assert relfro(host(layer.d_w2), bw["dW2"]) <= t
+    assert relfro(host(layer.d_x), bw["dX"]) <= t
+    assert relfro(host(layer.d_w_gate), bw["dWg"]) <= t
