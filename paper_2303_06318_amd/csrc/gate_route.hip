@@ -52,15 +52,16 @@ __device__ __forceinline__ void softmax_top1_row(const float *row, int rstride, 
 }
 
 // ------------------------------------------------------------------ fused gate, bf16 tokens
-// Workgroup: 256 threads = 4 waves, 16*R tokens.  Wave w takes k-steps w, w+4, ... (32 k each);
-// the four partial [16R x Epad] tiles are summed through LDS in a fixed order.
-template <int NT, int R>
-__global__ __launch_bounds__(256) void gate_bf16_kernel(const bf16_t *x, const bf16_t *planes, const float *bias,
+// Workgroup: NW waves, 16*R tokens.  Wave w takes k-steps w, w+NW, ... (32 k each); the NW partial
+// [16R x Epad] tiles are summed through LDS in a fixed order.  The three planes of Wg are read from
+// L2 once per workgroup, so R is chosen large enough that this traffic stays below that of X.
+template <int NT, int R, int NW, int U>
+__global__ __launch_bounds__(64 * NW) void gate_bf16_kernel(const bf16_t *x, const bf16_t *planes, const float *bias,
                                                          float *logits, float *probs, int32_t *expert,
                                                          float *gate_p, int64_t T, int h, int E) {
     constexpr int EP = NT * 16;
     constexpr int TM = 16 * R;
-    __shared__ float part[4][TM][EP + 1];
+    __shared__ float part[NW][TM][EP + 1];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t t0 = (int64_t)blockIdx.x * TM;
     const int i16 = lane & 15, g = lane >> 4;
@@ -74,7 +75,6 @@ __global__ __launch_bounds__(256) void gate_bf16_kernel(const bf16_t *x, const b
 
     // Buffer resources: rows beyond the last token and k beyond h read as zero, so the loop has no
     // branches and U k-steps of loads are in flight per wave before their MFMAs issue.
-    constexpr int U = 4;
     constexpr uint32_t OOB = 0x80000000u;
     const int64_t rows = T - t0 < TM ? T - t0 : TM;
     const __amdgpu_buffer_rsrc_t xr =
@@ -82,12 +82,12 @@ __global__ __launch_bounds__(256) void gate_bf16_kernel(const bf16_t *x, const b
     const __amdgpu_buffer_rsrc_t pr =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(planes), 0, (int)(3 * plane * 2), 0x00020000);
     const int nsteps = (h + 31) / 32;
-    for (int s = wave; s < nsteps; s += 4 * U) {
+    for (int s = wave; s < nsteps; s += NW * U) {
         bf16x8 a[U][R];
         uint32_t koff[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int k = (s + 4 * u) * 32 + g * 8;
+            const int k = (s + NW * u) * 32 + g * 8;
             koff[u] = k < h ? (uint32_t)k * 2u : OOB;
 #pragma unroll
             for (int r = 0; r < R; ++r)
@@ -121,9 +121,11 @@ __global__ __launch_bounds__(256) void gate_bf16_kernel(const bf16_t *x, const b
 #pragma unroll
             for (int v = 0; v < 4; ++v) part[wave][r * 16 + g * 4 + v][n * 16 + i16] = acc[r][n][v];
     __syncthreads();
-    for (int idx = tid; idx < TM * E; idx += 256) {
+    for (int idx = tid; idx < TM * E; idx += 64 * NW) {
         int tt = idx / E, j = idx - tt * E;
-        float v = ((part[0][tt][j] + part[1][tt][j]) + part[2][tt][j]) + part[3][tt][j];
+        float v = part[0][tt][j];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) v += part[w][tt][j];
         if (bias) v += bias[j];
         part[0][tt][j] = v;
         if (t0 + tt < T) logits[(t0 + tt) * E + j] = v;
@@ -246,12 +248,28 @@ size_t gate_ws_bytes(const moe_shape_t *sh) {
     return ((planes + 255) / 256) * 256 + ((hist + 255) / 256) * 256;
 }
 
-template <int NT, int R>
+// tokens per workgroup / 16, waves per workgroup and k-steps in flight per wave, by number of 16-expert tiles
+#ifndef GATE_R1
+#define GATE_R1 4
+#define GATE_NW1 8
+#define GATE_U1 4
+#endif
+#ifndef GATE_R2
+#define GATE_R2 4
+#define GATE_NW2 8
+#define GATE_U2 2
+#endif
+#ifndef GATE_R4
+#define GATE_R4 4
+#define GATE_NW4 8
+#define GATE_U4 2
+#endif
+template <int NT, int R, int NW, int U>
 static void launch_gate_bf16(const moe_shape_t *sh, const void *x, const bf16_t *planes, const float *bias,
                              float *logits, float *probs, int32_t *expert, float *gate_p, hipStream_t s) {
     const int TM = 16 * R;
     dim3 grid((unsigned)((sh->T + TM - 1) / TM));
-    hipLaunchKernelGGL((gate_bf16_kernel<NT, R>), grid, dim3(256), 0, s, (const bf16_t *)x, planes, bias, logits,
+    hipLaunchKernelGGL((gate_bf16_kernel<NT, R, NW, U>), grid, dim3(64 * NW), 0, s, (const bf16_t *)x, planes, bias, logits,
                        probs, expert, gate_p, sh->T, sh->h, sh->E);
 }
 
@@ -277,11 +295,11 @@ moe_status_t run_gate(const moe_shape_t *sh, const void *x, const float *w_gate,
         hipLaunchKernelGGL(gate_split_wg_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, w_gate, planes,
                            sh->h, sh->E, NT * 16);
         switch (NT) {
-            case 1: launch_gate_bf16<1, 2>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
-            case 2: launch_gate_bf16<2, 2>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
-            case 4: launch_gate_bf16<4, 2>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
-            case 8: launch_gate_bf16<8, 1>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
-            default: launch_gate_bf16<16, 1>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
+            case 1: launch_gate_bf16<1, GATE_R1, GATE_NW1, GATE_U1>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
+            case 2: launch_gate_bf16<2, GATE_R2, GATE_NW2, GATE_U2>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
+            case 4: launch_gate_bf16<4, GATE_R4, GATE_NW4, GATE_U4>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
+            case 8: launch_gate_bf16<8, 1, 4, 4>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
+            default: launch_gate_bf16<16, 1, 4, 4>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
         }
     }
     moe_status_t st = check_launch("gate");
