@@ -34,7 +34,8 @@
  *
  * Pins: see tests/test_oracle_*.py (brute force routing, one-hot cumsum
  * formulation, library matmul/softmax/GeLU in fp64, autograd through a dense
- * one-hot formulation, finite differences, the paper's 4-token example).
+ * one-hot formulation, finite differences, the paper's 4-token example; for the optimizer step at
+ * the end of this file: a library AdamW in fp64, closed forms of the first step, tiling invariance).
  */
 #include <math.h>
 #include <stdint.h>
@@ -275,6 +276,68 @@ void orc_gate_bwd(int64_t T, int32_t h, int32_t E, const double *dp, const float
             dXg[t * h + k] = acc;
         }
     }
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Tiled mixed-precision AdamW step (paper: Section 4 -- the optimizer up-casts the 16-bit
+ * gradients of the expert parameter group to 32 bit before the update; done for the whole group
+ * at once this needs a temporary of 4 bytes per parameter, so the group is cut into tiles of ts
+ * parameters that are processed one after the other, and the temporary of 4*ts bytes is reused
+ * by every tile.  The optimizer is AdamW: experimental set-up, Section 6).
+ *
+ * Per tile, in the paper's order:
+ *   1. up-cast: staging[j] = fp32(grad[i0 + j]) * grad_mult        (fp32 storage, ts floats)
+ *   2. update from staging, element by element (decoupled weight decay, bias-corrected moments):
+ *        m <- b1 m + (1 - b1) g            v <- b2 v + (1 - b2) g^2
+ *        mhat = m / (1 - b1^t)             vhat = v / (1 - b2^t)
+ *        w <- w - lr * ( mhat / (sqrt(vhat) + eps) + wd * w )
+ *      evaluated in double from the fp32 values of g, m, v, w; m, v, w are stored as fp32 (the
+ *      optimizer states of mixed precision training are 32 bit);
+ *   3. the 16-bit copy of the parameter is the fp32 master value rounded to nearest even bf16
+ *      (round_bf16 != 0) or the fp32 value itself.
+ * Readings the paper leaves open: the decay term is scaled by lr (the form every framework the
+ * paper builds on uses); grad_mult is the inverse loss scale (1 for bf16); t counts from 1.
+ *
+ * staging must hold ts floats and nothing else is used as temporary, which is the memory bound
+ * of Section 4; touched_hi (optional) receives the highest staging index written + 1.
+ * ------------------------------------------------------------------------------------------ */
+static float round_to_bf16(float x) {
+    uint32_t u;
+    memcpy(&u, &x, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return x;            /* NaN stays NaN */
+    uint32_t keep = u >> 16, rest = u & 0xffffu;
+    if (rest > 0x8000u || (rest == 0x8000u && (keep & 1u))) keep += 1u;
+    u = keep << 16;
+    float y;
+    memcpy(&y, &u, 4);
+    return y;
+}
+
+void orc_adamw_tiled(int64_t n, int64_t ts, double lr, double beta1, double beta2, double eps, double wd,
+                     int32_t step, double grad_mult, const float *grad, float *master, float *exp_avg,
+                     float *exp_avg_sq, float *param, int32_t round_bf16, float *staging, int64_t *touched_hi) {
+    const double bc1 = 1.0 - pow(beta1, (double)step);
+    const double bc2 = 1.0 - pow(beta2, (double)step);
+    int64_t hi = 0;
+    for (int64_t i0 = 0; i0 < n; i0 += ts) {
+        const int64_t len = (n - i0 < ts) ? (n - i0) : ts;
+        for (int64_t j = 0; j < len; ++j) staging[j] = (float)((double)grad[i0 + j] * grad_mult);
+        if (len > hi) hi = len;
+        for (int64_t j = 0; j < len; ++j) {
+            const int64_t i = i0 + j;
+            const double g = (double)staging[j];
+            const double m = beta1 * (double)exp_avg[i] + (1.0 - beta1) * g;
+            const double v = beta2 * (double)exp_avg_sq[i] + (1.0 - beta2) * g * g;
+            const double mhat = m / bc1, vhat = v / bc2;
+            const double w0 = (double)master[i];
+            const double w = w0 - lr * (mhat / (sqrt(vhat) + eps) + wd * w0);
+            exp_avg[i] = (float)m;
+            exp_avg_sq[i] = (float)v;
+            master[i] = (float)w;
+            param[i] = round_bf16 ? round_to_bf16(master[i]) : master[i];
+        }
+    }
+    if (touched_hi) *touched_hi = hi;
 }
 
 int orc_max_threads(void) {

@@ -58,6 +58,8 @@ def lib():
         L.orc_dispatch_bwd.argtypes = [i64, i32, i64, p, p, p, p]
         L.orc_gate_bwd.argtypes = [i64, i32, i32] + [p] * 8
         L.orc_max_threads.restype = C.c_int
+        L.orc_adamw_tiled.restype = None
+        L.orc_adamw_tiled.argtypes = [i64, i64, dbl, dbl, dbl, dbl, dbl, i32, dbl] + [p] * 5 + [i32, p, p]
         for name in ("orc_gate_logits", "orc_top1_softmax", "orc_route", "orc_dispatch", "orc_ffn_fwd",
                      "orc_combine", "orc_combine_bwd", "orc_ffn_bwd", "orc_dispatch_bwd", "orc_gate_bwd"):
             getattr(L, name).restype = None
@@ -204,6 +206,28 @@ def gate_bwd(dp, probs, expert, x, wg):
     lib().orc_gate_bwd(T, h, E, _p(dp), _p(probs), _p(_a(expert, np.int32)), _p(x), _p(wg), _p(dL), _p(dWg),
                        _p(dXg))
     return dL, dWg, dXg
+
+
+def adamw_tiled(grad, master, exp_avg, exp_avg_sq, ts: int, lr: float, beta1: float, beta2: float, eps: float,
+                weight_decay: float, step: int, grad_mult: float = 1.0, round_bf16: bool = True):
+    """One tiled mixed-precision AdamW step (paper Section 4; AdamW per the set-up in Section 6).
+
+    ``grad`` holds the 16-bit gradients as float32 values; ``master``, ``exp_avg``, ``exp_avg_sq``
+    are float32 and are NOT modified: the new (master, exp_avg, exp_avg_sq, param, staging_len) are
+    returned, staging_len being the number of staging floats the step touched (<= ts).
+    """
+    grad = _a(grad, np.float32).ravel()
+    w = np.array(master, dtype=np.float32).ravel().copy()
+    m = np.array(exp_avg, dtype=np.float32).ravel().copy()
+    v = np.array(exp_avg_sq, dtype=np.float32).ravel().copy()
+    n = grad.size
+    assert w.size == n and m.size == n and v.size == n and ts >= 1 and step >= 1
+    param = np.empty(n, np.float32)
+    staging = np.empty(ts, np.float32)
+    hi = C.c_int64(0)
+    lib().orc_adamw_tiled(n, ts, lr, beta1, beta2, eps, weight_decay, step, grad_mult, _p(grad), _p(w), _p(m),
+                          _p(v), _p(param), 1 if round_bf16 else 0, _p(staging), C.addressof(hi))
+    return w, m, v, param, int(hi.value)
 
 
 def max_threads() -> int:

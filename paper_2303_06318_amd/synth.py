@@ -28,6 +28,7 @@ from dataclasses import dataclass, field
 import numpy as np
 
 TENSOR_X, TENSOR_WG, TENSOR_W1, TENSOR_W2, TENSOR_DOUT = 0, 1, 2, 3, 4
+TENSOR_OPT_GRAD, TENSOR_OPT_MASTER, TENSOR_OPT_M, TENSOR_OPT_V = 5, 6, 7, 8
 _ROW_BLOCK = 4096
 
 
@@ -147,3 +148,44 @@ def scaled(wl: Workload, **kw) -> Workload:
     d = dict(wl.__dict__)
     d.update(kw)
     return Workload(**d)
+
+
+@dataclass
+class OptimizerInputs:
+    """State of a flat parameter group before an optimizer step (all arrays have n elements)."""
+    grad: np.ndarray           # fp32 values of the stored gradients (bf16-representable if dtype is bf16)
+    master: np.ndarray         # fp32 master weights
+    exp_avg: np.ndarray        # fp32 first moment
+    exp_avg_sq: np.ndarray     # fp32 second moment, >= 0
+    grad_bits: np.ndarray | None   # uint16 bf16 patterns of grad (bf16 only)
+
+
+_OPT_BLOCK = 1 << 20
+
+
+def make_optimizer_inputs(n: int, seed: int, dtype: str = "bf16", *, w_std: float = 0.02, g_std: float = 1e-3,
+                          zero_fraction: float = 0.01, threads: int = 8) -> OptimizerInputs:
+    """A flat expert-parameter group in mid-training: weights N(0, w_std) like the layer's expert
+    weights, gradients N(0, g_std) with a fraction set to exactly zero (columns of an expert whose
+    buffer rows were empty), a first moment of the gradients' scale and a second moment that is the
+    square of a draw of that scale.  Streams are per 2**20-element block, so a prefix of a larger
+    group equals the smaller group."""
+    nb = (n + _OPT_BLOCK - 1) // _OPT_BLOCK
+
+    def flat(tid, std):
+        parts = _draw_chunks(seed, tid, nb, lambda c: (min(_OPT_BLOCK, n - c * _OPT_BLOCK),), std, threads)
+        return np.concatenate(parts) if parts else np.zeros((0,), np.float32)
+
+    grad = flat(TENSOR_OPT_GRAD, g_std)
+    master = flat(TENSOR_OPT_MASTER, w_std)
+    m = flat(TENSOR_OPT_M, 0.3 * g_std)
+    v = flat(TENSOR_OPT_V, g_std)
+    np.square(v, out=v)
+    if zero_fraction > 0.0 and n:
+        period = max(1, int(round(1.0 / zero_fraction)))
+        grad[seed % period::period] = 0.0
+    bits = None
+    if dtype == "bf16":
+        bits = round_to_bf16_bits(grad)
+        grad = bf16_bits_to_f32(bits)
+    return OptimizerInputs(grad, master, m, v, bits)
