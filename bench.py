@@ -32,6 +32,48 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_GEMM_TRAFFIC_BYTES = {"cfg5_6p7b_tp4_fwdbwd": 1.399e9}
 
 
+def bench_optimizer(args, wl, layer, w1, w2):
+    """Tiled mixed-precision AdamW step over the layer's expert parameters (two flat groups, W1 and W2, of
+    E*h*f parameters each), with the gradients the last backward left in HBM.  Three variants of the same
+    step: the paper's tiling with its fp32 staging tile (ts parameters), the same with a 16x larger tile,
+    and the up-cast done in registers (no temporary).  Algorithmic bytes per parameter: 14 read + 14
+    written (bf16 gradient and parameter copy, fp32 master weight and two moments)."""
+    import torch
+    from paper_2303_06318_amd import moe
+    groups = []
+    for w, g in ((w1, layer.d_w1), (w2, layer.d_w2)):
+        gf = g.reshape(-1).float()
+        groups.append(dict(n=w.numel(), grad=g.reshape(-1), master=w.reshape(-1).float(), m=0.3 * gf, v=gf * gf,
+                           param=torch.empty_like(w.reshape(-1))))
+        del gf
+    n_total = sum(gr["n"] for gr in groups)
+    big_ts = 16 * args.tile_size
+    staging = torch.empty(big_ts, dtype=torch.float32, device="cuda")
+    res = {"params": n_total, "groups": len(groups), "dtype": "f32 update, bf16 gradients and parameter copy",
+           "bytes_per_param": 28, "peak_GBs": PEAK_HBM_GBS}
+    step_no = 0
+    for name, ts, stg in (("tiled", args.tile_size, staging), ("tiled_16x", big_ts, staging), ("register_upcast", 1, None)):
+        ms = []
+        for it in range(2 + 5):
+            step_no += 1
+            hp = moe.make_adamw(3e-4, 0.9, 0.95, 1e-8, 0.1, step_no)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for gr in groups:
+                moe.moe_adamw_tiled(gr["n"], ts, hp, gr["grad"], gr["master"], gr["m"], gr["v"], gr["param"], stg,
+                                    moe.MOE_BF16)
+            e1.record()
+            torch.cuda.synchronize()
+            if it >= 2:
+                ms.append(e0.elapsed_time(e1))
+        t = sum(ms) / len(ms)
+        gbs = 28.0 * n_total / (t * 1e-3) / 1e9
+        res[name] = {"ts": None if stg is None else ts, "temporary_bytes": 0 if stg is None else 4 * min(ts, groups[0]["n"]),
+                     "launches": len(groups) * (1 if stg is None else 2 * -(-groups[0]["n"] // ts)),
+                     "ms": round(t, 4), "GBs": round(gbs, 1), "frac": round(gbs / PEAK_HBM_GBS, 4)}
+    return res
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -42,6 +84,10 @@ def main() -> int:
     ap.add_argument("--cpu-sample-tokens", type=int, default=768)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (known size) so that HBM counters can be scaled")
+    ap.add_argument("--optimizer", action="store_true",
+                    help="also time the tiled AdamW step over this layer's expert parameters (reported in an extra "
+                         "\"optimizer\" object; never part of ms_per_step)")
+    ap.add_argument("--tile-size", type=int, default=1_800_000, help="ts of the tiled optimizer step")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU's share of the layer on ONE GPU; --gpus must be 1 "
@@ -171,6 +217,10 @@ def main() -> int:
                                   f"({'fwd+bwd' if wl.backward else 'fwd'}, all {wl.E} experts, capacity {Cs}), "
                                   f"{tc1 - tc0:.1f} s"}
 
+    optimizer = None
+    if args.optimizer:
+        optimizer = bench_optimizer(args, wl, layer, w1, w2)
+
     out = {
         "metric": "MoE-layer tokens/sec " + ("fwd+bwd" if wl.backward else "fwd") + f" at h={wl.h},E={wl.E} (1 GPU)",
         "value": round(wl.T / (ms_per_step * 1e-3), 1),
@@ -193,6 +243,8 @@ def main() -> int:
         "phase_ms": {p: round(v, 4) for p, v in phase_ms.items()},
         "hbm_frac_of_8TBs": hbm_frac,
     }
+    if optimizer is not None:
+        out["optimizer"] = optimizer
     print(json.dumps(out))
     return 0
 

@@ -2,7 +2,8 @@
  * moe.h -- C ABI of the MI355X (gfx950) library for one GPU's share of a TED
  * Mixture-of-Experts layer: top-1 gate, capacity-limited routing, dispatch into
  * per-expert buffers, the per-expert FFN shard (GEMM, GeLU, GEMM), the
- * gate-weighted combine, and the backward of all of these.
+ * gate-weighted combine, and the backward of all of these; plus the tiled optimizer
+ * step for the expert parameters (last entry point).
  *
  * Paper: "A Hybrid Tensor-Expert-Data Parallelism Approach to Optimize
  * Mixture-of-Experts Training" (DeepSpeed-TED).  The layer is Section 1 /
@@ -193,6 +194,39 @@ moe_status_t moe_dispatch_bwd(const moe_shape_t *shape, const void *d_buf, const
 moe_status_t moe_gate_bwd(const moe_shape_t *shape, const float *d_gate_p, const float *probs,
                           const int32_t *expert, const void *x, const float *w_gate, float *d_logits,
                           float *d_w_gate, void *d_x_accum, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Tiled mixed-precision AdamW step for a flat group of n expert parameters.
+ * Paper, Section 4: before the update the optimizer up-casts the 16-bit gradients to 32 bit; for the
+ * expert parameter group that temporary is 4 bytes per parameter, so the group is cut into tiles of
+ * ts parameters, processed one after the other, and one temporary of 4*ts bytes serves every tile
+ * (the paper fixes ts = 1.8 million).  The optimizer is AdamW (Section 6, set-up).
+ * Per parameter i, with t = hp->step >= 1:
+ *   g   = fp32(grad[i]) * hp->grad_mult               (the up-cast; grad_mult = inverse loss scale, 1 = none)
+ *   m   = beta1 m + (1 - beta1) g ;   v = beta2 v + (1 - beta2) g^2
+ *   w   = w - lr * ( (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps) + weight_decay * w )
+ *   param[i] = dtype(w)                                (round to nearest even for bf16)
+ * evaluated in fp32; master, exp_avg, exp_avg_sq are updated in place.
+ *   grad [n] dtype, master [n] f32 (in/out), exp_avg [n] f32 (in/out), exp_avg_sq [n] f32 (in/out),
+ *   param [n] dtype (out), hp: host pointer, read before the call returns.
+ *   staging: [min(ts, n)] f32 device buffer, the ONLY temporary of the step, contents undefined
+ *   afterwards; for each tile the up-cast gradients are written there and the update reads them.
+ *   staging == NULL: the up-cast happens in registers inside the update, no temporary exists and ts
+ *   is ignored.  Both ways, and every ts, give bit-identical results.
+ * With a staging buffer and ts < n, ts must be a multiple of 8.  n = 0 is a no-op.
+ * Errors: MOE_ERR_INVALID_ARG for NULL / misaligned arrays, ts < 1, step < 1, beta outside [0, 1),
+ * negative or non-finite lr, eps, weight_decay; MOE_ERR_UNSUPPORTED for n >= 2^40, a ts that is not a
+ * multiple of 8, or an unknown dtype.
+ */
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay;
+    float grad_mult;   /* multiplies every gradient during the up-cast */
+    int32_t step;      /* t: 1 for the first update */
+} moe_adamw_t;
+
+moe_status_t moe_adamw_tiled(int64_t n, int64_t ts, const moe_adamw_t *hp, const void *grad, float *master,
+                             float *exp_avg, float *exp_avg_sq, void *param, float *staging, int32_t dtype,
+                             void *stream);
 
 #ifdef __cplusplus
 }

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmoe_ted.so")
-SOURCES = ["moe_api.hip", "gate_route.hip", "permute.hip", "gate_bwd.hip", "gemm_f32.hip", "gemm_bf16.hip"]
+SOURCES = ["moe_api.hip", "gate_route.hip", "permute.hip", "gate_bwd.hip", "gemm_f32.hip", "gemm_bf16.hip", "adamw.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

@@ -42,6 +42,11 @@ moe_status_t run_gate_bwd(const moe_shape_t *, const float *, const float *, con
                           const float *, float *, float *, void *, void *, hipStream_t);
 moe_status_t run_dispatch_bwd_fused(const moe_shape_t *, const void *, const int32_t *, const int32_t *, void *,
                                     const float *, const float *, hipStream_t);
+struct AdamwConst {
+    float lr, beta1, beta2, omb1, omb2, eps, wd, inv_bc1, inv_bc2, grad_mult;
+};
+moe_status_t run_adamw_tiled(int64_t, int64_t, const AdamwConst &, const void *, float *, float *, float *, void *,
+                             float *, int, hipStream_t);
 moe_status_t run_gate_dx_f32(const moe_shape_t *, const float *, const float *, void *, hipStream_t);
 
 static size_t esize(const moe_shape_t *sh) { return sh->dtype == MOE_BF16 ? 2 : 4; }
@@ -432,6 +437,62 @@ moe_status_t moe_gate_bwd(const moe_shape_t *shape, const float *d_gate_p, const
     if (st != MOE_OK) return st;
     return run_gate_bwd(shape, d_gate_p, probs, expert, x, w_gate, d_logits, d_w_gate, d_x_accum, ws,
                         (hipStream_t)stream);
+}
+
+moe_status_t moe_adamw_tiled(int64_t n, int64_t ts, const moe_adamw_t *hp, const void *grad, float *master,
+                             float *exp_avg, float *exp_avg_sq, void *param, float *staging, int32_t dtype,
+                             void *stream) {
+    if (hp == nullptr) {
+        set_error("moe_adamw_tiled: hp is NULL");
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (n < 0 || ts < 1 || hp->step < 1) {
+        set_error("moe_adamw_tiled: n=%lld ts=%lld step=%d (need n >= 0, ts >= 1, step >= 1)", (long long)n,
+                  (long long)ts, hp->step);
+        return MOE_ERR_INVALID_ARG;
+    }
+    auto ok_nonneg = [](float v) { return std::isfinite(v) && v >= 0.0f; };
+    if (!(hp->beta1 >= 0.0f && hp->beta1 < 1.0f) || !(hp->beta2 >= 0.0f && hp->beta2 < 1.0f) || !ok_nonneg(hp->lr) ||
+        !ok_nonneg(hp->eps) || !ok_nonneg(hp->weight_decay) || !std::isfinite(hp->grad_mult)) {
+        set_error("moe_adamw_tiled: hyperparameters out of range (lr=%g beta1=%g beta2=%g eps=%g weight_decay=%g "
+                  "grad_mult=%g)", hp->lr, hp->beta1, hp->beta2, hp->eps, hp->weight_decay, hp->grad_mult);
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (dtype != MOE_F32 && dtype != MOE_BF16) {
+        set_error("moe_adamw_tiled: unknown dtype %d", dtype);
+        return MOE_ERR_UNSUPPORTED;
+    }
+    if (n >= ((int64_t)1 << 40)) {
+        set_error("moe_adamw_tiled: n=%lld is beyond the supported 2^40", (long long)n);
+        return MOE_ERR_UNSUPPORTED;
+    }
+    if (n == 0) return MOE_OK;
+    REQUIRE_PTR(grad);
+    REQUIRE_PTR(master);
+    REQUIRE_PTR(exp_avg);
+    REQUIRE_PTR(exp_avg_sq);
+    REQUIRE_PTR(param);
+    OPTIONAL_PTR(staging);
+    if (staging != nullptr && ts < n && ts % 8 != 0) {
+        set_error("moe_adamw_tiled: ts=%lld must be a multiple of 8 when the group has more than one tile",
+                  (long long)ts);
+        return MOE_ERR_UNSUPPORTED;
+    }
+    // constants in double, rounded once; 1 - beta is exact in fp32 for beta in [0.5, 1)
+    const double bc1 = 1.0 - std::pow((double)hp->beta1, (double)hp->step);
+    const double bc2 = 1.0 - std::pow((double)hp->beta2, (double)hp->step);
+    AdamwConst c;
+    c.lr = hp->lr;
+    c.beta1 = hp->beta1;
+    c.beta2 = hp->beta2;
+    c.omb1 = (float)(1.0 - (double)hp->beta1);
+    c.omb2 = (float)(1.0 - (double)hp->beta2);
+    c.eps = hp->eps;
+    c.wd = hp->weight_decay;
+    c.inv_bc1 = (float)(1.0 / bc1);
+    c.inv_bc2 = (float)(1.0 / bc2);
+    c.grad_mult = hp->grad_mult;
+    return run_adamw_tiled(n, ts, c, grad, master, exp_avg, exp_avg_sq, param, staging, dtype, (hipStream_t)stream);
 }
 
 }  // extern "C"

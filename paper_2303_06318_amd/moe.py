@@ -19,12 +19,17 @@ MOE_GELU_ERF, MOE_GELU_TANH = 0, 1
 
 EXPORTS = ["moe_capacity", "moe_workspace_bytes", "moe_status_string", "moe_last_error", "moe_version", "moe_gate",
            "moe_dispatch", "moe_expert_ffn_fwd", "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd",
-           "moe_dispatch_bwd", "moe_gate_bwd"]
+           "moe_dispatch_bwd", "moe_gate_bwd", "moe_adamw_tiled"]
 
 
 class Shape(C.Structure):
     _fields_ = [("T", C.c_int64), ("h", C.c_int32), ("E", C.c_int32), ("f", C.c_int32), ("C", C.c_int64),
                 ("dtype", C.c_int32), ("act", C.c_int32)]
+
+
+class AdamwParams(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float), ("grad_mult", C.c_float), ("step", C.c_int32)]
 
 
 class MoeError(RuntimeError):
@@ -62,6 +67,7 @@ def lib():
             "moe_expert_ffn_bwd": [sp] + [vp] * 10 + [vp, sz, vp],
             "moe_dispatch_bwd": [sp] + [vp] * 6 + [vp],
             "moe_gate_bwd": [sp] + [vp] * 8 + [vp, sz, vp],
+            "moe_adamw_tiled": [i64, i64, C.POINTER(AdamwParams)] + [vp] * 6 + [i32, vp],
         }
         for name, args in sig.items():
             fn = getattr(L, name)
@@ -156,3 +162,13 @@ def moe_gate_bwd(shape, d_gate_p, probs, expert, x, w_gate, d_logits, d_w_gate, 
     _check(lib().moe_gate_bwd(C.byref(shape), _ptr(d_gate_p), _ptr(probs), _ptr(expert), _ptr(x), _ptr(w_gate),
                               _ptr(d_logits), _ptr(d_w_gate), _ptr(d_x_accum), _ptr(ws), _nbytes(ws),
                               _stream(stream)))
+
+
+def make_adamw(lr, beta1, beta2, eps, weight_decay, step, grad_mult=1.0) -> AdamwParams:
+    return AdamwParams(float(lr), float(beta1), float(beta2), float(eps), float(weight_decay), float(grad_mult),
+                       int(step))
+
+
+def moe_adamw_tiled(n, ts, hp, grad, master, exp_avg, exp_avg_sq, param, staging, dtype=MOE_BF16, stream=None):
+    _check(lib().moe_adamw_tiled(int(n), int(ts), C.byref(hp), _ptr(grad), _ptr(master), _ptr(exp_avg),
+                                 _ptr(exp_avg_sq), _ptr(param), _ptr(staging), int(dtype), _stream(stream)))

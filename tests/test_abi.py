@@ -79,6 +79,35 @@ def test_null_misaligned_and_workspace_errors():
     assert moe.status_string(st) == "MOE_ERR_WORKSPACE_TOO_SMALL"
 
 
+@pytest.mark.parametrize("kw,status,word", [
+    (dict(step=0), moe.MOE_ERR_INVALID_ARG, "step"),
+    (dict(ts=0), moe.MOE_ERR_INVALID_ARG, "ts"),
+    (dict(n=-1), moe.MOE_ERR_INVALID_ARG, "n="),
+    (dict(beta1=1.0), moe.MOE_ERR_INVALID_ARG, "beta1"),
+    (dict(lr=float("nan")), moe.MOE_ERR_INVALID_ARG, "lr"),
+    (dict(eps=-1e-8), moe.MOE_ERR_INVALID_ARG, "eps"),
+    (dict(dtype=5), moe.MOE_ERR_UNSUPPORTED, "dtype"),
+    (dict(n=1 << 40), moe.MOE_ERR_UNSUPPORTED, "2^40"),
+    (dict(ts=1001), moe.MOE_ERR_UNSUPPORTED, "multiple of 8"),
+    (dict(master=None), moe.MOE_ERR_INVALID_ARG, "master"),
+    (dict(staging=4100), moe.MOE_ERR_INVALID_ARG, "aligned"),
+])
+def test_adamw_bad_arguments_are_rejected_without_launch(kw, status, word):
+    a = 4096      # never dereferenced: validation fails first
+    args = dict(n=100000, ts=1000, lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1, step=1, dtype=moe.MOE_BF16,
+                master=a, staging=a)
+    args.update(kw)
+    hp = moe.make_adamw(args["lr"], args["beta1"], args["beta2"], args["eps"], args["weight_decay"], args["step"])
+    with pytest.raises(moe.MoeError) as ei:
+        moe.moe_adamw_tiled(args["n"], args["ts"], hp, a, args["master"], a, a, a, args["staging"], args["dtype"], stream=0)
+    assert ei.value.status == status and word in str(ei.value)
+
+
+def test_adamw_empty_group_is_a_no_op():
+    hp = moe.make_adamw(1e-3, 0.9, 0.95, 1e-8, 0.1, 1)
+    moe.moe_adamw_tiled(0, 8, hp, None, None, None, None, None, None, moe.MOE_BF16, stream=0)
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(moe, "_lib", None)
     monkeypatch.setattr(moe, "LIB_PATH", "/nonexistent/libmoe_ted.so")
