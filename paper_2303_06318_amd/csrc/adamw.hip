@@ -20,8 +20,10 @@ struct AdamwConst {
 };
 
 constexpr int OPT_THREADS = 256;
-constexpr int OPT_VEC = 8;                         // parameters per thread and step: one 16-byte bf16 load
-constexpr int OPT_UNROLL = 1;                      // groups of 8 per thread (1, 2 and 4 stream equally fast)
+constexpr int OPT_VEC = 4;                         // parameters per thread and group: one 16-byte fp32 access per array,
+                                                   // so every wave-wide load or store covers one contiguous KB
+constexpr int OPT_UNROLL = 1;                      // groups per thread, OPT_THREADS * OPT_VEC parameters apart
+                                                   // (2 and 4 stream no faster and make small tiles slower)
 constexpr int64_t OPT_PER_BLOCK = (int64_t)OPT_THREADS * OPT_VEC * OPT_UNROLL;
 
 // Plain loads and stores: non-temporal ones were measured 15-30 % slower for this stream.
@@ -54,30 +56,38 @@ __device__ __forceinline__ void store_param(void *param, int64_t i, float w) {
     else ((float *)param)[i] = w;
 }
 
+template <bool BF16>
+__device__ __forceinline__ void load_grad4(const void *grad, int64_t i, float (&g)[OPT_VEC]) {
+    if constexpr (BF16) {
+        const bf16x4 gv = ld_stream((const bf16x4 *)((const bf16_t *)grad + i));
+#pragma unroll
+        for (int k = 0; k < OPT_VEC; ++k) g[k] = bf16_to_f32(gv[k]);
+    } else {
+        const f32x4 gv = ld_stream((const f32x4 *)((const float *)grad + i));
+#pragma unroll
+        for (int k = 0; k < OPT_VEC; ++k) g[k] = gv[k];
+    }
+}
+
 // staging[j] = fp32(grad[j]) * grad_mult for j < len
 template <bool BF16>
 __global__ __launch_bounds__(OPT_THREADS) void upcast_kernel(int64_t len, const void *__restrict__ grad, float mult,
                                                              float *__restrict__ staging) {
     const int64_t base = (int64_t)blockIdx.x * OPT_PER_BLOCK + (int64_t)threadIdx.x * OPT_VEC;
+    float g[OPT_UNROLL][OPT_VEC];
+#pragma unroll
+    for (int u = 0; u < OPT_UNROLL; ++u) {
+        const int64_t i = base + (int64_t)u * OPT_THREADS * OPT_VEC;
+        if (i + OPT_VEC <= len) load_grad4<BF16>(grad, i, g[u]);
+    }
 #pragma unroll
     for (int u = 0; u < OPT_UNROLL; ++u) {
         const int64_t i = base + (int64_t)u * OPT_THREADS * OPT_VEC;
         if (i + OPT_VEC <= len) {
-            float g[OPT_VEC];
-            if constexpr (BF16) {
-                const bf16x8 gv = *(const bf16x8 *)((const bf16_t *)grad + i);
+            f32x4 o;
 #pragma unroll
-                for (int k = 0; k < OPT_VEC; ++k) g[k] = bf16_to_f32(gv[k]);
-            } else {
-                const f32x4 a = *(const f32x4 *)((const float *)grad + i), b = *(const f32x4 *)((const float *)grad + i + 4);
-#pragma unroll
-                for (int k = 0; k < 4; ++k) { g[k] = a[k]; g[4 + k] = b[k]; }
-            }
-            f32x4 o0, o1;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) { o0[k] = g[k] * mult; o1[k] = g[4 + k] * mult; }
-            *(f32x4 *)(staging + i) = o0;
-            *(f32x4 *)(staging + i + 4) = o1;
+            for (int k = 0; k < OPT_VEC; ++k) o[k] = g[u][k] * mult;
+            st_stream((f32x4 *)(staging + i), o);
         } else {
             for (int64_t j = i; j < len && j < i + OPT_VEC; ++j) staging[j] = load_grad<BF16>(grad, j) * mult;
         }
@@ -92,65 +102,45 @@ __global__ __launch_bounds__(OPT_THREADS) void adamw_kernel(int64_t len, AdamwCo
                                                             float *__restrict__ exp_avg_sq, void *__restrict__ param) {
     const int64_t base = (int64_t)blockIdx.x * OPT_PER_BLOCK + (int64_t)threadIdx.x * OPT_VEC;
     float g[OPT_UNROLL][OPT_VEC];
-    float w[OPT_UNROLL][OPT_VEC], m[OPT_UNROLL][OPT_VEC], v[OPT_UNROLL][OPT_VEC];
-    // all loads of the thread first, so that every group's 7 requests are in flight together
+    f32x4 wv[OPT_UNROLL], mv[OPT_UNROLL], vv[OPT_UNROLL];
+    // all loads of the thread first, so that every group's requests are in flight together
 #pragma unroll
     for (int u = 0; u < OPT_UNROLL; ++u) {
         const int64_t i = base + (int64_t)u * OPT_THREADS * OPT_VEC;
         if (i + OPT_VEC <= len) {
-            if constexpr (BF16 && !STAGED) {
-                const bf16x8 gv = ld_stream((const bf16x8 *)((const bf16_t *)gsrc + i));
-#pragma unroll
-                for (int k = 0; k < OPT_VEC; ++k) g[u][k] = bf16_to_f32(gv[k]);
-            } else {
-                const f32x4 a = ld_stream((const f32x4 *)((const float *)gsrc + i)), b = ld_stream((const f32x4 *)((const float *)gsrc + i + 4));
-#pragma unroll
-                for (int k = 0; k < 4; ++k) { g[u][k] = a[k]; g[u][4 + k] = b[k]; }
-            }
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                const f32x4 wq = ld_stream((const f32x4 *)(master + i + 4 * q));
-                const f32x4 mq = ld_stream((const f32x4 *)(exp_avg + i + 4 * q));
-                const f32x4 vq = ld_stream((const f32x4 *)(exp_avg_sq + i + 4 * q));
-#pragma unroll
-                for (int k = 0; k < 4; ++k) { w[u][4 * q + k] = wq[k]; m[u][4 * q + k] = mq[k]; v[u][4 * q + k] = vq[k]; }
-            }
+            load_grad4<(BF16 && !STAGED)>(gsrc, i, g[u]);
+            wv[u] = ld_stream((const f32x4 *)(master + i));
+            mv[u] = ld_stream((const f32x4 *)(exp_avg + i));
+            vv[u] = ld_stream((const f32x4 *)(exp_avg_sq + i));
         }
     }
 #pragma unroll
     for (int u = 0; u < OPT_UNROLL; ++u) {
         const int64_t i = base + (int64_t)u * OPT_THREADS * OPT_VEC;
         if (i + OPT_VEC <= len) {
+            float w[OPT_VEC], m[OPT_VEC], v[OPT_VEC];
 #pragma unroll
             for (int k = 0; k < OPT_VEC; ++k) {
+                w[k] = wv[u][k]; m[k] = mv[u][k]; v[k] = vv[u][k];
                 const float gk = STAGED ? g[u][k] : g[u][k] * c.grad_mult;
-                adamw_one(c, gk, w[u][k], m[u][k], v[u][k]);
+                adamw_one(c, gk, w[k], m[k], v[k]);
             }
+            f32x4 wq, mq, vq;
 #pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                f32x4 wq, mq, vq;
-#pragma unroll
-                for (int k = 0; k < 4; ++k) { wq[k] = w[u][4 * q + k]; mq[k] = m[u][4 * q + k]; vq[k] = v[u][4 * q + k]; }
-                st_stream((f32x4 *)(master + i + 4 * q), wq);
-                st_stream((f32x4 *)(exp_avg + i + 4 * q), mq);
-                st_stream((f32x4 *)(exp_avg_sq + i + 4 * q), vq);
-            }
+            for (int k = 0; k < OPT_VEC; ++k) { wq[k] = w[k]; mq[k] = m[k]; vq[k] = v[k]; }
+            st_stream((f32x4 *)(master + i), wq);
+            st_stream((f32x4 *)(exp_avg + i), mq);
+            st_stream((f32x4 *)(exp_avg_sq + i), vq);
             if constexpr (BF16) {
-                bf16x8 pv;
+                bf16x4 pv;
 #pragma unroll
-                for (int k = 0; k < OPT_VEC; ++k) pv[k] = f32_to_bf16(w[u][k]);
-                st_stream((bf16x8 *)((bf16_t *)param + i), pv);
+                for (int k = 0; k < OPT_VEC; ++k) pv[k] = f32_to_bf16(w[k]);
+                st_stream((bf16x4 *)((bf16_t *)param + i), pv);
             } else {
-#pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    f32x4 wq;
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) wq[k] = w[u][4 * q + k];
-                    st_stream((f32x4 *)((float *)param + i + 4 * q), wq);
-                }
+                st_stream((f32x4 *)((float *)param + i), wq);
             }
         } else {
-            // ragged end of the tile: at most 7 parameters, one at a time
+            // ragged end of the tile: at most 3 parameters, one at a time
             for (int64_t j = i; j < len && j < i + OPT_VEC; ++j) {
                 float gj = STAGED ? ((const float *)gsrc)[j] : load_grad<BF16>(gsrc, j) * c.grad_mult;
                 float wj = master[j], mj = exp_avg[j], vj = exp_avg_sq[j];
