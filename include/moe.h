@@ -114,7 +114,11 @@ moe_status_t moe_gate(const moe_shape_t *shape, const void *x, const float *w_ga
 /*
  * Dispatch (Section 3, step 4, local half: tokens are grouped by destination expert into
  * equal-size chunks, which is the send layout of the all-to-all).
- *   buf[e,s,:] = x[token_of_slot[e,s],:]  for filled slots, 0 for empty ones.
+ *   buf[e,s,:] = x[token_of_slot[e,s],:]  for filled slots (s < kept[e]).
+ * Empty slots (s >= kept[e]) are NOT written: the padding of an expert's chunk carries no
+ * information, nothing in this library reads it (every later step takes kept[e] rows), and
+ * filling it would add up to (capacity_factor - 1) / capacity_factor of the step's HBM writes.
+ * A caller that ships whole chunks to another GPU clears buf once when it allocates it.
  *   x [T,h], token_of_slot [E,C], buf [E,C,h].
  */
 moe_status_t moe_dispatch(const moe_shape_t *shape, const void *x, const int32_t *token_of_slot, void *buf,
@@ -150,7 +154,8 @@ moe_status_t moe_combine(const moe_shape_t *shape, const void *y, const int32_t 
 /*
  * Combine backward.
  *   d_y[e_t,s_t,:] = gate_p[t] * d_out[t,:] ;  d_gate_p[t] = <d_out[t,:], y[e_t,s_t,:]>
- *   for kept tokens; d_gate_p[t] = 0 for dropped tokens; empty slots of d_y are set to 0.
+ *   for kept tokens; d_gate_p[t] = 0 for dropped tokens; empty slots of d_y (s >= kept[e]) are
+ *   not written (moe_expert_ffn_bwd reads kept[e] rows per expert).
  *   d_out [T,h], y [E,C,h], token_of_slot [E,C], gate_p [T], d_y [E,C,h], d_gate_p [T] f32.
  */
 moe_status_t moe_combine_bwd(const moe_shape_t *shape, const void *d_out, const void *y,

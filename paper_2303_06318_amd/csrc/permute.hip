@@ -33,19 +33,16 @@ template <> struct Vec<bf16_t> {
     }
 };
 
-// buf[r,:] = x[token_of_slot[r],:] or 0.  Pure copy: works on 16-byte words of any type.
+// buf[r,:] = x[token_of_slot[r],:] for filled slots; empty slots are left alone (no later step reads
+// them).  Pure copy: works on 16-byte words of any type.
 __global__ __launch_bounds__(256) void dispatch_kernel(const u32x4 *x, const int32_t *token_of_slot, u32x4 *buf,
                                                         int64_t rows, int words) {
     for (int64_t r = blockIdx.x; r < rows; r += gridDim.x) {
         const int tok = token_of_slot[r];
+        if (tok < 0) continue;
         u32x4 *dst = buf + r * words;
-        if (tok >= 0) {
-            const u32x4 *src = x + (int64_t)tok * words;
-            for (int i = threadIdx.x; i < words; i += 256) dst[i] = src[i];
-        } else {
-            const u32x4 z = {0u, 0u, 0u, 0u};
-            for (int i = threadIdx.x; i < words; i += 256) dst[i] = z;
-        }
+        const u32x4 *src = x + (int64_t)tok * words;
+        for (int i = threadIdx.x; i < words; i += 256) dst[i] = src[i];
     }
 }
 
@@ -91,8 +88,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const u32x4 *y, const int3
     }
 }
 
-// d_y[r,:] = p * d_out[tok,:];  d_gate_p[tok] = <d_out[tok,:], y[r,:]>;  empty rows -> 0;
-// dropped tokens get d_gate_p = 0.
+// d_y[r,:] = p * d_out[tok,:];  d_gate_p[tok] = <d_out[tok,:], y[r,:]>;  empty rows are left alone
+// (the backward GEMMs read kept rows only); dropped tokens get d_gate_p = 0.
 template <typename T>
 __global__ __launch_bounds__(256) void combine_bwd_kernel(const u32x4 *d_out, const u32x4 *y,
                                                            const int32_t *token_of_slot, const int32_t *slot,
@@ -104,12 +101,8 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const u32x4 *d_out, co
         if (slot[t] < 0) d_gate_p[t] = 0.f;
     for (int64_t r = blockIdx.x; r < rows; r += gridDim.x) {
         const int tok = token_of_slot[r];
+        if (tok < 0) continue;
         u32x4 *o = d_y + r * words;
-        if (tok < 0) {
-            const u32x4 z = {0u, 0u, 0u, 0u};
-            for (int i = threadIdx.x; i < words; i += 256) o[i] = z;
-            continue;
-        }
         const float p = gate_p[tok];
         const u32x4 *g = d_out + (int64_t)tok * words;
         const u32x4 *yy = y + r * words;

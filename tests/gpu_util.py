@@ -45,7 +45,23 @@ class DevInputs:
 def make_layer(wl: synth.Workload, backward=None, act=moe.MOE_GELU_ERF) -> MoeLayer:
     dt = moe.MOE_BF16 if wl.dtype == "bf16" else moe.MOE_F32
     bw = wl.backward if backward is None else backward
-    return MoeLayer(wl.T, wl.h, wl.E, wl.f, wl.C, dt, act, backward=bw)
+    layer = MoeLayer(wl.T, wl.h, wl.E, wl.f, wl.C, dt, act, backward=bw)
+    poison(layer)
+    return layer
+
+
+def poison(layer: MoeLayer) -> None:
+    """Fill every intermediate buffer and the workspace with NaN bit patterns (all bytes 0xFF), so that a
+    kernel that read a row nobody wrote (a slot beyond kept[e]) would show up as NaN in the results."""
+    for name in ("buf", "hact", "z_save", "y", "d_y", "d_buf", "ws", "out", "d_x", "d_w1", "d_w2"):
+        t = getattr(layer, name, None)
+        if t is not None:
+            t.view(torch.uint8).fill_(0xFF)
+
+
+def kept_rows(a: np.ndarray, kept) -> np.ndarray:
+    """Rows [0, kept[e]) of every expert of an [E, C, ...] array, concatenated."""
+    return np.concatenate([a[e, :int(k)] for e, k in enumerate(kept)], axis=0)
 
 
 def tol(wl: synth.Workload) -> float:
