@@ -47,10 +47,23 @@ def bench_optimizer(args, wl, layer, w1, w2):
                            param=torch.empty_like(w.reshape(-1))))
         del gf
     n_total = sum(gr["n"] for gr in groups)
+    cpu = None
+    if not args.no_cpu_baseline:
+        # the oracle's step on the first 16 M parameters of the first group, from the same state
+        from oracle import moe_oracle as orc
+        S = min(16 << 20, groups[0]["n"])
+        h_ = {k: groups[0][k][:S].float().cpu().numpy() for k in ("grad", "master", "m", "v")}
+        tc0 = time.perf_counter()
+        orc.adamw_tiled(h_["grad"], h_["master"], h_["m"], h_["v"], ts=args.tile_size, lr=3e-4, beta1=0.9, beta2=0.95,
+                        eps=1e-8, weight_decay=0.1, step=1)
+        tc1 = time.perf_counter()
+        cpu = {"value": round(S / (tc1 - tc0), 1), "unit": "params/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {S} parameters of W1's group, one step, ts = {args.tile_size}, {tc1 - tc0:.2f} s"}
+        del h_
     big_ts = 16 * args.tile_size
     staging = torch.empty(big_ts, dtype=torch.float32, device="cuda")
     res = {"params": n_total, "groups": len(groups), "dtype": "f32 update, bf16 gradients and parameter copy",
-           "bytes_per_param": 28, "peak_GBs": PEAK_HBM_GBS}
+           "bytes_per_param": 28, "peak_GBs": PEAK_HBM_GBS, "cpu_baseline": cpu}
     step_no = 0
     for name, ts, stg in (("tiled", args.tile_size, staging), ("tiled_16x", big_ts, staging), ("register_upcast", 1, None)):
         ms = []
@@ -68,7 +81,7 @@ def bench_optimizer(args, wl, layer, w1, w2):
                 ms.append(e0.elapsed_time(e1))
         t = sum(ms) / len(ms)
         gbs = 28.0 * n_total / (t * 1e-3) / 1e9
-        res[name] = {"ts": None if stg is None else ts, "temporary_bytes": 0 if stg is None else 4 * min(ts, groups[0]["n"]),
+        res[name] = {"params_per_s": round(n_total / (t * 1e-3), 1), "ts": None if stg is None else ts, "temporary_bytes": 0 if stg is None else 4 * min(ts, groups[0]["n"]),
                      "launches": len(groups) * (1 if stg is None else 2 * -(-groups[0]["n"] // ts)),
                      "ms": round(t, 4), "GBs": round(gbs, 1), "frac": round(gbs / PEAK_HBM_GBS, 4)}
     return res
