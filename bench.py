@@ -193,7 +193,7 @@ def main() -> int:
     # (kept rows only); 2 launches in ffn_fwd, 4 in ffn_bwd.
     n_launch = 2 + (4 if wl.backward else 0)
     gemm_ms = phase_ms["ffn_fwd"] + (phase_ms["ffn_bwd"] if wl.backward else 0.0)
-    flops_per_launch = 2.0 * wl.h * wl.f * n_kept
+    flops_per_launch = 2.0 * wl.hm * wl.fm * n_kept      # model sizes: zero padding to a multiple of 8 is not work
     avg_launch_ms = gemm_ms / n_launch
     achieved = flops_per_launch / (avg_launch_ms * 1e-3) / 1e12
     traffic = MEASURED_GEMM_TRAFFIC_BYTES.get(wl.name)
@@ -204,14 +204,14 @@ def main() -> int:
 
     esz = 2
     hbm = {
-        "gate": (wl.T * wl.h * esz + wl.h * wl.E * 4 + wl.T * wl.E * 4 * (2 if wl.backward else 1) + wl.T * 8),
-        "dispatch": 2 * n_kept * wl.h * esz + wl.T * 8,
-        "combine": n_kept * wl.h * esz + wl.T * wl.h * esz + wl.T * 12,
+        "gate": (wl.T * wl.hm * esz + wl.hm * wl.E * 4 + wl.T * wl.E * 4 * (2 if wl.backward else 1) + wl.T * 8),
+        "dispatch": 2 * n_kept * wl.hm * esz + wl.T * 8,
+        "combine": n_kept * wl.hm * esz + wl.T * wl.hm * esz + wl.T * 12,
     }
     if wl.backward:
-        hbm["combine_bwd"] = 3 * n_kept * wl.h * esz
-        hbm["dispatch_bwd"] = n_kept * wl.h * esz + wl.T * wl.h * esz      # gate's d_x term fused in
-        hbm["gate_bwd"] = wl.T * wl.h * esz + wl.T * wl.E * 4 * 2           # d_logits, d_w_gate (reads x once)
+        hbm["combine_bwd"] = 3 * n_kept * wl.hm * esz
+        hbm["dispatch_bwd"] = n_kept * wl.hm * esz + wl.T * wl.hm * esz      # gate's d_x term fused in
+        hbm["gate_bwd"] = wl.T * wl.hm * esz + wl.T * wl.E * 4 * 2           # d_logits, d_w_gate (reads x once)
     hbm_frac = {p: round(b / (phase_ms[p] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) for p, b in hbm.items()}
 
     cpu_baseline = None
@@ -235,7 +235,7 @@ def main() -> int:
         optimizer = bench_optimizer(args, wl, layer, w1, w2)
 
     out = {
-        "metric": "MoE-layer tokens/sec " + ("fwd+bwd" if wl.backward else "fwd") + f" at h={wl.h},E={wl.E} (1 GPU)",
+        "metric": "MoE-layer tokens/sec " + ("fwd+bwd" if wl.backward else "fwd") + f" at h={wl.hm},E={wl.E} (1 GPU)",
         "value": round(wl.T / (ms_per_step * 1e-3), 1),
         "unit": "tokens/s",
         "n_gpus": 1,
@@ -247,7 +247,8 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": wl.name, "T": wl.T, "h": wl.h, "E": wl.E, "f": wl.f, "C": wl.C,
+        "config": {"workload": wl.name, "T": wl.T, "h": wl.hm, "E": wl.E, "f": wl.fm, "h_stored": wl.h, "f_stored": wl.f,
+                   "C": wl.C,
                    "capacity_factor": wl.capacity_factor, "n_kept": n_kept,
                    "count_min": int(counts.min()), "count_max": int(counts.max()), "seed": wl.seed,
                    "pass": "fwd+bwd" if wl.backward else "fwd"},

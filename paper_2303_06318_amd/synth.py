@@ -47,10 +47,23 @@ class Workload:
     wg_std: float
     zipf_bias: bool = False
     backward: bool = False
+    # model sizes when the stored sizes h, f are those sizes rounded up to the library's multiple of 8:
+    # columns h_model..h-1 of x / d_out / w2, rows h_model..h-1 of wg / w1, columns f_model..f-1 of w1 and
+    # rows f_model..f-1 of w2 are drawn as zeros, which leaves every result of the model-size layer unchanged
+    h_model: int = 0
+    f_model: int = 0
 
     @property
     def C(self) -> int:
         return int(math.ceil(float(self.capacity_factor) * float(self.T) / float(self.E)))
+
+    @property
+    def hm(self) -> int:
+        return self.h_model or self.h
+
+    @property
+    def fm(self) -> int:
+        return self.f_model or self.f
 
 
 WORKLOADS = {
@@ -61,6 +74,12 @@ WORKLOADS = {
                                 zipf_bias=True),
     "cfg5_6p7b_tp4_fwdbwd": Workload("cfg5_6p7b_tp4_fwdbwd", 16384, 4096, 16, 4096, 1.25, "bf16", 4, 1.0, 0.02,
                                      0.02, backward=True),
+    # the other two base models of the weak-scaling study (Section 7.4: 16 experts, tensor-parallel degrees 2 and 8;
+    # Table 1: hidden sizes 2560 and 5140).  5140 and 4 * 5140 / 8 = 2570 are not multiples of 8: stored zero-padded.
+    "cfg6_2p7b_tp2_fwdbwd": Workload("cfg6_2p7b_tp2_fwdbwd", 16384, 2560, 16, 5120, 1.25, "bf16", 5, 1.0, 0.02, 0.02,
+                                     backward=True),
+    "cfg7_13b_tp8_fwdbwd": Workload("cfg7_13b_tp8_fwdbwd", 16384, 5144, 16, 2576, 1.25, "bf16", 6, 1.0, 0.02, 0.02,
+                                    backward=True, h_model=5140, f_model=2570),
 }
 
 
@@ -129,6 +148,15 @@ def make_inputs(wl: Workload, *, experts: int | None = None, threads: int = 8,
     w2 = np.stack(_draw_chunks(wl.seed, TENSOR_W2, nE, lambda e: (wl.f, wl.h), wl.w_std, threads)) \
         if nE else np.zeros((0, wl.f, wl.h), np.float32)
     d_out = _token_tensor(wl.seed, TENSOR_DOUT, wl.T, wl.h, 1.0, threads) if wl.backward else None
+    if wl.hm < wl.h or wl.fm < wl.f:
+        x[:, wl.hm:] = 0
+        wg[wl.hm:, :] = 0
+        w1[:, wl.hm:, :] = 0
+        w1[:, :, wl.fm:] = 0
+        w2[:, wl.fm:, :] = 0
+        w2[:, :, wl.hm:] = 0
+        if d_out is not None:
+            d_out[:, wl.hm:] = 0
     bits = {}
     if wl.dtype == "bf16":
         for name in ("x", "w1", "w2", "d_out"):

@@ -30,7 +30,8 @@ def sample_rows(kept, n, rng):
     return sorted(set(picks))
 
 
-@pytest.mark.parametrize("name", ["cfg2_1p3b_fwd", "cfg3_6p7b_tp4_fwd", "cfg4_skewed_fwd", "cfg5_6p7b_tp4_fwdbwd"])
+@pytest.mark.parametrize("name", ["cfg2_1p3b_fwd", "cfg3_6p7b_tp4_fwd", "cfg4_skewed_fwd", "cfg5_6p7b_tp4_fwdbwd",
+                                  "cfg6_2p7b_tp2_fwdbwd", "cfg7_13b_tp8_fwdbwd"])
 def test_full_size(orc, name):
     wl = W[name]
     rng = np.random.default_rng(7)
@@ -88,15 +89,19 @@ def test_full_size(orc, name):
     # ---------------- backward ----------------
     d_y_g, d_buf_g, dp_g = host(layer.d_y), host(layer.d_buf), host(layer.d_gate_p)
     z_g = host(layer.z_save)
+    dp_got, dp_want = [], []
     for e, (rs, Z, H, Y) in ZHY.items():
         toks = tok_o[e, rs]
         dY = p_o[toks, None].astype(np.float64) * inp.d_out[toks].astype(np.float64)
         assert relfro(d_y_g[e, rs], dY) <= t
-        dp = (inp.d_out[toks].astype(np.float64) * Y).sum(1)
-        assert relfro(dp_g[toks], dp) <= t
+        # d_gate_p is a dot product over h whose terms cancel: a single value can be far smaller than its
+        # rounding error, so the sampled values are compared as one vector, after the loop
+        dp_got.append(dp_g[toks])
+        dp_want.append((inp.d_out[toks].astype(np.float64) * Y).sum(1))
         assert relfro(z_g[e, rs], orc.act_grad_array(Z)) <= t     # z_save holds GeLU'(z)
         dD, _, _, _ = orc.ffn_bwd(dY, D[e, rs], Z, H, inp.w1[e], inp.w2[e])
         assert relfro(d_buf_g[e, rs], dD) <= t, (e, "d_buf")
+    assert relfro(np.concatenate(dp_got), np.concatenate(dp_want)) <= t
     # weight gradients: a few columns of f for two experts, over all kept rows
     for e in (0, wl.E - 1):
         k = int(kept_o[e])

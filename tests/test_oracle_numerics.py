@@ -300,3 +300,29 @@ def test_synth_generator_is_seeded_and_bf16_exact():
     # per-expert streams do not depend on how many experts are drawn
     c = synth.make_inputs(wl, experts=1)
     assert np.array_equal(c.w1[0], a.w1[0])
+
+
+def test_zero_padding_of_h_and_f_changes_nothing(orc):
+    """A model whose sizes are not multiples of 8 (13B base: h = 5140, f = 2570) is stored zero-padded; the padded
+    layer must give the model-size layer's results in the model's columns and zeros in the padding."""
+    hm, fm, E, T = 20, 10, 3, 64
+    wl = synth.Workload("pad", T, 24, E, 16, 1.0, "f32", 9, 1.0, 0.3, 0.5, backward=True, h_model=hm, f_model=fm)
+    a = synth.make_inputs(wl)
+    assert not a.x[:, hm:].any() and not a.w1[:, hm:, :].any() and not a.w1[:, :, fm:].any()
+    assert not a.w2[:, fm:, :].any() and not a.w2[:, :, hm:].any() and not a.wg[hm:].any() and not a.d_out[:, hm:].any()
+    fw_p = orc.layer_forward(a.x, a.wg, a.w1, a.w2, wl.C)
+    bw_p = orc.layer_backward(fw_p, a.d_out, a.x, a.wg, a.w1, a.w2)
+    c = np.ascontiguousarray
+    x, wg, w1, w2, do = c(a.x[:, :hm]), c(a.wg[:hm]), c(a.w1[:, :hm, :fm]), c(a.w2[:, :fm, :hm]), c(a.d_out[:, :hm])
+    fw = orc.layer_forward(x, wg, w1, w2, wl.C)
+    bw = orc.layer_backward(fw, do, x, wg, w1, w2)
+    assert np.array_equal(fw["expert"], fw_p["expert"]) and np.array_equal(fw["slot"], fw_p["slot"])
+    assert np.allclose(fw_p["out"][:, :hm], fw["out"], rtol=1e-12, atol=1e-300) and not fw_p["out"][:, hm:].any()
+    assert np.allclose(bw_p["dX"][:, :hm], bw["dX"], rtol=1e-12, atol=1e-300) and not bw_p["dX"][:, hm:].any()
+    assert np.allclose(bw_p["dW1"][:, :hm, :fm], bw["dW1"], rtol=1e-12, atol=1e-300)
+    assert np.allclose(bw_p["dW2"][:, :fm, :hm], bw["dW2"], rtol=1e-12, atol=1e-300)
+    assert np.allclose(bw_p["dWg"][:hm], bw["dWg"], rtol=1e-12, atol=1e-300)
+    # every padded weight entry has a zero gradient (GeLU(0) = 0 and W2's padded rows are zero), so the padding
+    # stays zero under training
+    assert not bw_p["dW1"][:, hm:, :].any() and not bw_p["dW1"][:, :, fm:].any()
+    assert not bw_p["dW2"][:, :, hm:].any() and not bw_p["dW2"][:, fm:, :].any() and not bw_p["dWg"][hm:].any()
