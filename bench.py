@@ -100,6 +100,8 @@ def main() -> int:
     ap.add_argument("--optimizer", action="store_true",
                     help="also time the tiled AdamW step over this layer's expert parameters (reported in an extra "
                          "\"optimizer\" object; never part of ms_per_step)")
+    ap.add_argument("--recompute", action="store_true",
+                    help="activation recomputation: hact and z_save are not kept, the backward runs GEMM1 again")
     ap.add_argument("--tile-size", type=int, default=1_800_000, help="ts of the tiled optimizer step")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -128,7 +130,8 @@ def main() -> int:
     x, w1, w2, d_out = up("x"), up("w1"), up("w2"), up("d_out")
     wg = torch.from_numpy(inp.wg).cuda()
     bias = None if inp.logit_bias is None else torch.from_numpy(inp.logit_bias).cuda()
-    layer = MoeLayer(wl.T, wl.h, wl.E, wl.f, wl.C, moe.MOE_BF16, moe.MOE_GELU_ERF, backward=wl.backward)
+    layer = MoeLayer(wl.T, wl.h, wl.E, wl.f, wl.C, moe.MOE_BF16, moe.MOE_GELU_ERF, backward=wl.backward,
+                     recompute=args.recompute)
     sh = layer.shape
 
     phases = ["gate", "dispatch", "ffn_fwd", "combine"] + (
@@ -191,7 +194,7 @@ def main() -> int:
     n_kept = int(kept.sum())
     # dominant kernel: the grouped bf16 MFMA GEMM.  Algorithmic flops per launch = 2*h*f*N_kept
     # (kept rows only); 2 launches in ffn_fwd, 4 in ffn_bwd.
-    n_launch = 2 + (4 if wl.backward else 0)
+    n_launch = 2 + ((5 if args.recompute else 4) if wl.backward else 0)
     gemm_ms = phase_ms["ffn_fwd"] + (phase_ms["ffn_bwd"] if wl.backward else 0.0)
     flops_per_launch = 2.0 * wl.hm * wl.fm * n_kept      # model sizes: zero padding to a multiple of 8 is not work
     avg_launch_ms = gemm_ms / n_launch
@@ -251,7 +254,7 @@ def main() -> int:
                    "C": wl.C,
                    "capacity_factor": wl.capacity_factor, "n_kept": n_kept,
                    "count_min": int(counts.min()), "count_max": int(counts.max()), "seed": wl.seed,
-                   "pass": "fwd+bwd" if wl.backward else "fwd"},
+                   "pass": "fwd+bwd" if wl.backward else "fwd", "activation_recomputation": bool(args.recompute)},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "phase_ms": {p: round(v, 4) for p, v in phase_ms.items()},

@@ -81,8 +81,10 @@ typedef struct {
 int64_t moe_capacity(int64_t T, int32_t E, double capacity_factor);
 
 /* Bytes of device workspace the calls below need for this shape (one workspace serves
- * all calls of a layer; contents need not survive between calls except as noted).
- * 0 on a bad shape. */
+ * all calls of a layer; contents need not survive between calls).
+ * for_backward: 0 = forward only, 1 = forward and backward, 2 = forward and backward with
+ * activation recomputation (moe_expert_ffn_fwd called with hact = NULL, moe_expert_ffn_bwd with
+ * hact = z_save = NULL).  0 on a bad shape or mode. */
 size_t moe_workspace_bytes(const moe_shape_t *shape, int for_backward);
 
 const char *moe_status_string(moe_status_t s);
@@ -130,11 +132,14 @@ moe_status_t moe_dispatch(const moe_shape_t *shape, const void *x, const int32_t
  * second, so y is a partial sum that step 6's all-reduce would complete).
  *   for r < kept[e]:  z = buf[e,r,:] w1[e] ;  hact = GeLU(z) ;  y[e,r,:] = hact w2[e]
  * Rows r >= kept[e] of hact, z_save and y are not written.
- *   buf [E,C,h], w1 [E,h,f], w2 [E,f,h], kept [E], hact [E,C,f] (out, needed by backward),
+ *   buf [E,C,h], w1 [E,h,f], w2 [E,f,h], kept [E], y [E,C,h],
+ *   hact [E,C,f] (out; the backward needs it) or NULL: GeLU(z) then lives in the workspace only,
  *   z_save [E,C,f] or NULL (out, needed by backward: it receives GeLU'(z), the only function of
- *   the pre-activation the backward pass uses, so that backward does not evaluate erf again),
- *   y [E,C,h].
- * bf16: uses moe_workspace_bytes(shape, 0) bytes of workspace (tile plans of the two GEMMs).
+ *   the pre-activation the backward pass uses, so that backward does not evaluate erf again).
+ * hact = z_save = NULL is the forward of a layer trained with activation recomputation (the paper
+ * trains with activation checkpointing throughout, Section 5): between forward and backward only
+ * buf, y and the routing arrays are held; moe_expert_ffn_bwd recomputes the rest.
+ * Workspace: the tile plans of the two GEMMs (bf16), plus E*C*f*sizeof(dtype) when hact is NULL.
  */
 moe_status_t moe_expert_ffn_fwd(const moe_shape_t *shape, const void *buf, const void *w1, const void *w2,
                                 const int32_t *kept, void *z_save, void *hact, void *y, void *ws,
@@ -168,7 +173,11 @@ moe_status_t moe_combine_bwd(const moe_shape_t *shape, const void *d_out, const 
  *   d_w1[e] = buf^T d_z ;  d_buf = d_z w1[e]^T          (rows r < kept[e] only)
  * d_w1, d_w2 are overwritten (one micro-batch), in `dtype` with fp32 accumulation; an expert
  * with kept[e] = 0 gets zero gradients.  Rows r >= kept[e] of d_buf are not written.
- * Uses E*C*f*sizeof(dtype) bytes of workspace for d_z, plus (bf16) the tile plans of the four GEMMs.
+ * z_save = hact = NULL (both or neither): activation recomputation -- the forward's first GEMM is run
+ * again from buf and w1 and writes hact and GeLU'(z) into the workspace, then the backward proceeds
+ * as above; the results are bit-identical to the stored-activation call.
+ * Uses E*C*f*sizeof(dtype) bytes of workspace for d_z, plus (bf16) the tile plans of the GEMMs, plus
+ * 2*E*C*f*sizeof(dtype) when recomputing (moe_workspace_bytes(shape, 2)).
  */
 moe_status_t moe_expert_ffn_bwd(const moe_shape_t *shape, const void *d_y, const void *buf, const void *z_save,
                                 const void *hact, const void *w1, const void *w2, const int32_t *kept,

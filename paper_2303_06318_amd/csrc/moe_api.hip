@@ -160,14 +160,23 @@ static size_t ffn_plan_bytes(const moe_shape_t *sh, int first, int last) {
     for (int w = first; w <= last; ++w) n += gemm_bf16_plan_bytes(ffn_gemm(*sh, w));
     return n;
 }
-static size_t ffn_fwd_ws_bytes(const moe_shape_t *sh) { return ffn_plan_bytes(sh, G_FWD1, G_FWD2); }
-static size_t ffn_bwd_ws_bytes(const moe_shape_t *sh) { return dz_bytes(sh) + ffn_plan_bytes(sh, G_DH, G_DD); }
+// Workspace layouts of the FFN entry points ([E,C,f] arrays first, each rounded to 256 bytes, plans last):
+//   forward:   [hact if the caller keeps none][plans of GEMM1, GEMM2]
+//   backward:  [d_z][hact, GeLU'(z) if recomputed][plan of GEMM1 if recomputed][plans of the four backward GEMMs]
+static size_t ffn_fwd_ws_bytes(const moe_shape_t *sh, bool own_hact) {
+    return (own_hact ? dz_bytes(sh) : 0) + ffn_plan_bytes(sh, G_FWD1, G_FWD2);
+}
+static size_t ffn_bwd_ws_bytes(const moe_shape_t *sh, bool recompute) {
+    return dz_bytes(sh) * (recompute ? 3 : 1) + (recompute ? ffn_plan_bytes(sh, G_FWD1, G_FWD1) : 0) +
+           ffn_plan_bytes(sh, G_DH, G_DD);
+}
 
 static size_t ws_bytes_checked(const moe_shape_t *sh, int for_backward) {
+    const bool recompute = for_backward == 2;
     size_t need = gate_ws_bytes(sh);
-    if (ffn_fwd_ws_bytes(sh) > need) need = ffn_fwd_ws_bytes(sh);
+    if (ffn_fwd_ws_bytes(sh, recompute) > need) need = ffn_fwd_ws_bytes(sh, recompute);
     if (!for_backward) return need;
-    if (ffn_bwd_ws_bytes(sh) > need) need = ffn_bwd_ws_bytes(sh);
+    if (ffn_bwd_ws_bytes(sh, recompute) > need) need = ffn_bwd_ws_bytes(sh, recompute);
     if (round256(gate_bwd_ws_bytes(sh)) > need) need = round256(gate_bwd_ws_bytes(sh));
     return need;
 }
@@ -232,7 +241,7 @@ int64_t moe_capacity(int64_t T, int32_t E, double capacity_factor) {
 }
 
 size_t moe_workspace_bytes(const moe_shape_t *shape, int for_backward) {
-    if (check_shape(shape) != MOE_OK) return 0;
+    if (check_shape(shape) != MOE_OK || for_backward < 0 || for_backward > 2) return 0;
     return ws_bytes_checked(shape, for_backward);
 }
 
@@ -293,18 +302,20 @@ moe_status_t moe_expert_ffn_fwd(const moe_shape_t *shape, const void *buf, const
     REQUIRE_PTR(w2);
     REQUIRE_PTR(kept);
     OPTIONAL_PTR(z_save);
-    REQUIRE_PTR(hact);
+    OPTIONAL_PTR(hact);
     REQUIRE_PTR(y);
-    st = check_ws("moe_expert_ffn_fwd", ws, ws_bytes, ffn_fwd_ws_bytes(shape));
+    const bool own_hact = hact == nullptr;
+    st = check_ws("moe_expert_ffn_fwd", ws, ws_bytes, ffn_fwd_ws_bytes(shape, own_hact));
     if (st != MOE_OK) return st;
     const moe_shape_t &s = *shape;
     const bool bf = s.dtype == MOE_BF16;
     hipStream_t hs = (hipStream_t)stream;
+    if (own_hact) hact = ws;                   // not kept for the backward: it will be recomputed there
     GemmDesc g[2] = {ffn_gemm(s, G_FWD1), ffn_gemm(s, G_FWD2)};
     g[0].A = buf; g[0].B = w1; g[0].C = hact; g[0].C2 = z_save; g[0].kept = kept;
     g[1].A = hact; g[1].B = w2; g[1].C = y; g[1].kept = kept;
     if (bf) {
-        char *pl = (char *)ws;
+        char *pl = (char *)ws + (own_hact ? dz_bytes(shape) : 0);
         for (int i = 0; i < 2; ++i) { g[i].plan = pl; pl += gemm_bf16_plan_bytes(g[i]); }
         if ((st = launch_gemm_bf16_plans(g, 2, hs)) != MOE_OK) return st;
     }
@@ -346,20 +357,41 @@ moe_status_t moe_expert_ffn_bwd(const moe_shape_t *shape, const void *d_y, const
     if (st != MOE_OK) return st;
     REQUIRE_PTR(d_y);
     REQUIRE_PTR(buf);
-    REQUIRE_PTR(z_save);
-    REQUIRE_PTR(hact);
+    OPTIONAL_PTR(z_save);
+    OPTIONAL_PTR(hact);
     REQUIRE_PTR(w1);
     REQUIRE_PTR(w2);
     REQUIRE_PTR(kept);
     REQUIRE_PTR(d_buf);
     REQUIRE_PTR(d_w1);
     REQUIRE_PTR(d_w2);
-    st = check_ws("moe_expert_ffn_bwd", ws, ws_bytes, ffn_bwd_ws_bytes(shape));
+    if ((z_save == nullptr) != (hact == nullptr)) {
+        set_error("moe_expert_ffn_bwd: z_save and hact must be given together (or both NULL to recompute them)");
+        return MOE_ERR_INVALID_ARG;
+    }
+    const bool recompute = hact == nullptr;
+    st = check_ws("moe_expert_ffn_bwd", ws, ws_bytes, ffn_bwd_ws_bytes(shape, recompute));
     if (st != MOE_OK) return st;
     const moe_shape_t &s = *shape;
     const bool bf = s.dtype == MOE_BF16;
     hipStream_t hs = (hipStream_t)stream;
     void *d_z = ws;
+    char *after = (char *)ws + dz_bytes(shape);
+    if (recompute) {
+        // activation recomputation: the forward's first GEMM again, hact and GeLU'(z) into the workspace
+        void *hact_r = after, *zs_r = after + dz_bytes(shape);
+        after += 2 * dz_bytes(shape);
+        GemmDesc r = ffn_gemm(s, G_FWD1);
+        r.A = buf; r.B = w1; r.C = hact_r; r.C2 = zs_r; r.kept = kept;
+        if (bf) {
+            r.plan = after;
+            after += gemm_bf16_plan_bytes(r);
+            if ((st = launch_gemm_bf16_plans(&r, 1, hs)) != MOE_OK) return st;
+        }
+        if ((st = bf ? launch_gemm_bf16(r, hs) : launch_gemm_f32(r, hs)) != MOE_OK) return st;
+        hact = hact_r;
+        z_save = zs_r;
+    }
     GemmDesc g[4] = {ffn_gemm(s, G_DH), ffn_gemm(s, G_DW2), ffn_gemm(s, G_DW1), ffn_gemm(s, G_DD)};
     g[0].A = d_y; g[0].B = w2; g[0].C = d_z; g[0].Zin = z_save;
     g[1].A = hact; g[1].B = d_y; g[1].C = d_w2;
@@ -367,7 +399,7 @@ moe_status_t moe_expert_ffn_bwd(const moe_shape_t *shape, const void *d_y, const
     g[3].A = d_z; g[3].B = w1; g[3].C = d_buf;
     for (int i = 0; i < 4; ++i) g[i].kept = kept;
     if (bf) {
-        char *pl = (char *)ws + dz_bytes(shape);
+        char *pl = after;
         for (int i = 0; i < 4; ++i) { g[i].plan = pl; pl += gemm_bf16_plan_bytes(g[i]); }
         if ((st = launch_gemm_bf16_plans(g, 4, hs)) != MOE_OK) return st;
     }

@@ -12,7 +12,10 @@ from . import moe
 
 
 class MoeLayer:
-    def __init__(self, T, h, E, f, Cap, dtype=moe.MOE_BF16, act=moe.MOE_GELU_ERF, backward=False, device="cuda:0"):
+    def __init__(self, T, h, E, f, Cap, dtype=moe.MOE_BF16, act=moe.MOE_GELU_ERF, backward=False, device="cuda:0",
+                 recompute=False):
+        """recompute=True: activation recomputation -- hact and z_save are not held between forward and
+        backward (the backward recomputes them into the workspace)."""
         self.shape = moe.make_shape(T, h, E, f, Cap, dtype, act)
         self.T, self.h, self.E, self.f, self.C = T, h, E, f, Cap
         self.backward_enabled = backward
@@ -33,11 +36,12 @@ class MoeLayer:
         self.kept = empty((E,), i32)
         self.token_of_slot = empty((E, Cap), i32)
         self.buf = empty((E, Cap, h), td)
-        self.hact = empty((E, Cap, f), td)
-        self.z_save = empty((E, Cap, f), td) if backward else None
+        self.recompute = bool(recompute)
+        self.hact = None if recompute else empty((E, Cap, f), td)
+        self.z_save = empty((E, Cap, f), td) if backward and not recompute else None
         self.y = empty((E, Cap, h), td)
         self.out = empty((T, h), td)
-        nws = moe.moe_workspace_bytes(self.shape, backward)
+        nws = moe.moe_workspace_bytes(self.shape, 2 if recompute else (1 if backward else 0))
         if nws == 0:
             raise moe.MoeError(moe.MOE_ERR_UNSUPPORTED, moe.lib().moe_last_error().decode())
         self.ws = torch.empty((nws,), dtype=torch.uint8, device=dev)

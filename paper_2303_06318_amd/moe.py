@@ -113,8 +113,9 @@ def moe_capacity(T: int, E: int, capacity_factor: float) -> int:
     return int(lib().moe_capacity(int(T), int(E), float(capacity_factor)))
 
 
-def moe_workspace_bytes(shape: Shape, for_backward: bool) -> int:
-    return int(lib().moe_workspace_bytes(C.byref(shape), int(bool(for_backward))))
+def moe_workspace_bytes(shape: Shape, for_backward) -> int:
+    """for_backward: 0 / False forward only, 1 / True forward + backward, 2 with activation recomputation."""
+    return int(lib().moe_workspace_bytes(C.byref(shape), int(for_backward)))
 
 
 def moe_version() -> int:

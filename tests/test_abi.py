@@ -108,6 +108,24 @@ def test_adamw_empty_group_is_a_no_op():
     moe.moe_adamw_tiled(0, 8, hp, None, None, None, None, None, None, moe.MOE_BF16, stream=0)
 
 
+def test_recompute_mode_arguments():
+    sh = moe.make_shape(1024, 512, 8, 512, 128)
+    w0, w1, w2 = (moe.moe_workspace_bytes(sh, m) for m in (0, 1, 2))
+    assert 0 < w0 < w1 < w2 and moe.moe_workspace_bytes(sh, 3) == 0
+    assert w2 >= 3 * 8 * 128 * 512 * 2
+    a = 4096
+    L = moe.lib()
+    p = C.c_void_p(a)
+    # z_save without hact (or the reverse) is rejected
+    st = L.moe_expert_ffn_bwd(C.byref(sh), p, p, p, None, p, p, p, p, p, p, p, w2, None)
+    assert st == moe.MOE_ERR_INVALID_ARG and b"together" in L.moe_last_error()
+    # recomputation needs the larger workspace
+    st = L.moe_expert_ffn_bwd(C.byref(sh), p, p, None, None, p, p, p, p, p, p, p, w1, None)
+    assert st == moe.MOE_ERR_WORKSPACE_TOO_SMALL
+    st = L.moe_expert_ffn_fwd(C.byref(sh), p, p, p, p, None, None, p, p, w0, None)
+    assert st == moe.MOE_ERR_WORKSPACE_TOO_SMALL
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(moe, "_lib", None)
     monkeypatch.setattr(moe, "LIB_PATH", "/nonexistent/libmoe_ted.so")

@@ -273,3 +273,34 @@ def test_random_shapes(orc, wl):
     assert relfro(host(layer.d_w2), bw["dW2"]) <= t
     assert relfro(host(layer.d_x), bw["dX"]) <= t
     assert relfro(host(layer.d_w_gate), bw["dWg"]) <= t
+
+
+@pytest.mark.parametrize("name", ["cfg5_small", "f32_bwd", "bf16_bwd_9blocks", "bf16_bwd_E64"])
+def test_activation_recomputation_gives_identical_bits(orc, name):
+    """hact = z_save = NULL: the backward recomputes GEMM1 into the workspace; every result must equal the
+    stored-activation run bit for bit, and the recomputing layer holds no [E,C,f] array between the passes."""
+    wl = CASES[name]
+    inp = synth.make_inputs(wl)
+    dev = DevInputs(inp)
+    res = []
+    for recompute in (False, True):
+        dt = moe.MOE_BF16 if wl.dtype == "bf16" else moe.MOE_F32
+        layer = MoeLayer(wl.T, wl.h, wl.E, wl.f, wl.C, dt, moe.MOE_GELU_ERF, backward=True, recompute=recompute)
+        from gpu_util import poison
+        poison(layer)
+        layer.forward(dev.x, dev.wg, dev.w1, dev.w2, logit_bias=dev.bias)
+        # between the passes something else uses the workspace
+        layer.ws.fill_(0xFF)
+        layer.backward(dev.d_out, dev.x, dev.wg, dev.w1, dev.w2)
+        torch.cuda.synchronize()
+        assert (layer.hact is None) == recompute and (layer.z_save is None) == recompute
+        res.append([host(t) for t in (layer.out, layer.d_x, layer.d_w1, layer.d_w2, layer.d_w_gate, layer.d_buf)]
+                   + [host(layer.kept)])
+    kept = res[0][-1]
+    for a, b in zip(res[0][:5], res[1][:5]):
+        assert np.array_equal(a.view(np.uint32) if a.dtype == np.float32 else a, b.view(np.uint32) if b.dtype == np.float32 else b)
+    assert np.array_equal(kept_rows(res[0][5], kept).view(np.uint32), kept_rows(res[1][5], kept).view(np.uint32))
+    sh = moe.make_shape(wl.T, wl.h, wl.E, wl.f, wl.C, moe.MOE_BF16 if wl.dtype == "bf16" else moe.MOE_F32)
+    esz = 2 if wl.dtype == "bf16" else 4
+    extra = moe.moe_workspace_bytes(sh, 2) - moe.moe_workspace_bytes(sh, 1)
+    assert 0 < extra <= 2 * (wl.E * wl.C * wl.f * esz + 256) + 65536
