@@ -201,8 +201,8 @@ struct FragAddr {
 // expert with a few rows more than a multiple of 256 gets "tall" tiles of 9 blocks instead of an
 // extra tile that would stream a whole weight panel for a handful of rows.  An expert with at most
 // LIGHT_BLOCKS blocks is one "light" tile per column of n-tiles.
-// The heavy tiles form one list (expert, then n-tile, then m-tile, so that the m-tiles of one
-// weight panel are neighbours).  The list is cut into 8 contiguous shares of equal work (tile cost x
+// The heavy tiles form one list (expert -- in an order that alternates light and heavy experts --, then
+// n-tile, then m-tile, so that the m-tiles of one weight panel are neighbours).  The list is cut into 8 contiguous shares of equal work (tile cost x
 // k-tiles: experts differ in size), one per XCD, so that tiles which share a weight panel share an
 // L2; each share is followed by an eighth of the light tiles.  kept[] lives on the device, so a
 // small kernel writes the plan before every GEMM launch:
@@ -232,42 +232,56 @@ struct PlanArgs {
 
 __global__ __launch_bounds__(PLAN_THREADS) void gemm_plan_kernel(PlanArgs args) {
     const PlanDesc &p = args.p[blockIdx.x];
-    __shared__ int s_kept[256], s_nb[256], s_hv[256], s_nk[256];
+    __shared__ int s_kept[256], s_nb[256], s_hv[256], s_nk[256], s_eid[256];   // by list position, not by expert
     __shared__ int s_preH[257], s_preL[257];      // tiles of the experts before e (heavy, light)
     __shared__ long long s_preW[257], s_w[256];   // work of the heavy tiles of the experts before e, and of expert e
+    __shared__ long long s_w0[256];               // work by expert index, for the ordering
     __shared__ int s_ts[9], s_sl[9];              // split points of the heavy and of the light list
     const int tid = threadIdx.x, nt = p.nt;
+    int kx = 0, nb = 0, nkf = 1;
+    long long w = 0;
     if (tid < p.E) {
-        const int kx = p.kept[tid];
+        kx = p.kept[tid];
         const int Mx = p.rows_from_kept ? kx : p.M;
-        const int nb = (Mx + 31) >> 5;
+        nb = (Mx + 31) >> 5;
         const int nk = p.rows_from_kept ? 1 : (kx + BK - 1) / BK;
-        s_kept[tid] = kx;
-        s_nb[tid] = nb;
-        s_hv[tid] = nb > LIGHT_BLOCKS ? (nb + p.maxb - 1) / p.maxb : 0;
-        const int nkf = nk > 0 ? nk : 1;          // never 0: every heavy tile must fall into some share
-        s_nk[tid] = nkf;
-        long long w = 0;
+        nkf = nk > 0 ? nk : 1;                    // never 0: every heavy tile must fall into some share
         if (nb > LIGHT_BLOCKS) {  // one column of the expert's tiles: bx tiles of bb + 1 blocks, the others of bb
             const int hv = (nb + p.maxb - 1) / p.maxb, bb = nb / hv, bx = nb - bb * hv;
             w = (long long)(bx * tile_cost(bb + 1) + (hv - bx) * tile_cost(bb)) * nkf * nt;
         }
-        s_w[tid] = w;
+        s_w0[tid] = w;
+    }
+    __syncthreads();
+    if (tid < p.E) {
+        // Order of the experts in the list: lightest, heaviest, second lightest, second heaviest, ...  A share
+        // mostly holds whole experts (their tiles share weight panels), and with few experts per share the
+        // shares of a plain 0, 1, 2, ... order differ by the spread of the experts' sizes; pairing the extremes
+        // evens them out.  Any order gives the same results: tiles are independent.
+        int r = 0;
+        for (int e = 0; e < p.E; ++e) r += (s_w0[e] < w || (s_w0[e] == w && e < tid)) ? 1 : 0;
+        const int pos = r < (p.E + 1) / 2 ? 2 * r : 2 * (p.E - 1 - r) + 1;
+        s_eid[pos] = tid;
+        s_kept[pos] = kx;
+        s_nb[pos] = nb;
+        s_hv[pos] = nb > LIGHT_BLOCKS ? (nb + p.maxb - 1) / p.maxb : 0;
+        s_nk[pos] = nkf;
+        s_w[pos] = w;
     }
     __syncthreads();
     if (tid < p.E) {              // exclusive prefix sums, every thread for itself (E <= 256: no dependent chain)
         int h = 0, l = 0;
-        long long w = 0;
+        long long wp = 0;
         for (int e = 0; e < tid; ++e) {
             h += s_hv[e] * nt;
             l += (s_nb[e] > 0 && s_nb[e] <= LIGHT_BLOCKS) ? nt : 0;
-            w += s_w[e];
+            wp += s_w[e];
         }
-        s_preH[tid] = h; s_preL[tid] = l; s_preW[tid] = w;
+        s_preH[tid] = h; s_preL[tid] = l; s_preW[tid] = wp;
         if (tid == p.E - 1) {
             s_preH[p.E] = h + s_hv[tid] * nt;
             s_preL[p.E] = l + ((s_nb[tid] > 0 && s_nb[tid] <= LIGHT_BLOCKS) ? nt : 0);
-            s_preW[p.E] = w + s_w[tid];
+            s_preW[p.E] = wp + s_w[tid];
         }
     }
     __syncthreads();
@@ -283,10 +297,10 @@ __global__ __launch_bounds__(PLAN_THREADS) void gemm_plan_kernel(PlanArgs args) 
             while (s_preW[e + 1] < th) ++e;       // s_preW[e] < th <= s_preW[e + 1], so expert e is heavy
             const int mts = s_hv[e], bb = s_nb[e] / mts, bx = s_nb[e] - bb * mts;
             const int c1 = tile_cost(bb + 1), c0t = tile_cost(bb);
-            const long long w = (long long)(bx * c1 + (mts - bx) * c0t) * s_nk[e];   // work of one column of its tiles
-            const long long r = th - s_preW[e];                      // 1 .. w nt
-            const int c0 = (int)((r - 1) / w);                       // whole columns of n-tiles before
-            const int rem = (int)(((r - 1) - c0 * w) / s_nk[e]);     // cost inside the column, 0 .. w / nk - 1
+            const long long wc = (long long)(bx * c1 + (mts - bx) * c0t) * s_nk[e];   // work of one column of its tiles
+            const long long r = th - s_preW[e];                      // 1 .. wc nt
+            const int c0 = (int)((r - 1) / wc);                       // whole columns of n-tiles before
+            const int rem = (int)(((r - 1) - c0 * wc) / s_nk[e]);     // cost inside the column, 0 .. wc / nk - 1
             // tiles of the column whose preceding cost is at most rem
             int cm = rem < bx * c1 ? rem / c1 + 1 : bx + (rem - bx * c1) / c0t + 1;
             cm = cm < mts ? cm : mts;
@@ -325,7 +339,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void gemm_plan_kernel(PlanArgs args) 
         int4 ent;
         int pos;
         if (light) {
-            ent = make_int4(e | (s_nb[e] << 8) | (1 << 12), r, 0, s_kept[e]);
+            ent = make_int4(s_eid[e] | (s_nb[e] << 8) | (1 << 12), r, 0, s_kept[e]);
             pos = s_ts[x + 1] + s_sl[x] + (q - s_sl[x]);
         } else {
             const int mts = s_hv[e];
@@ -342,7 +356,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void gemm_plan_kernel(PlanArgs args) 
                 nti = ng * 8 + (rr - mti * gw);
             }
             const int nblk = bb + (mti < bx ? 1 : 0), blk0 = mti * bb + (mti < bx ? mti : bx);
-            ent = make_int4(e | (nblk << 8), nti, blk0, s_kept[e]);
+            ent = make_int4(s_eid[e] | (nblk << 8), nti, blk0, s_kept[e]);
             pos = s_ts[x] + s_sl[x] + (q - s_ts[x]);
         }
         tiles[pos] = ent;
