@@ -102,6 +102,9 @@ def main() -> int:
                          "\"optimizer\" object; never part of ms_per_step)")
     ap.add_argument("--recompute", action="store_true",
                     help="activation recomputation: hact and z_save are not kept, the backward runs GEMM1 again")
+    ap.add_argument("--fused", action="store_true",
+                    help="dispatch folded into GEMM1's operand load (forward-only workloads) and combine into GEMM2's "
+                         "epilogue (moe_expert_ffn_fwd_fused)")
     ap.add_argument("--tile-size", type=int, default=1_800_000, help="ts of the tiled optimizer step")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -134,35 +137,51 @@ def main() -> int:
                      recompute=args.recompute)
     sh = layer.shape
 
-    phases = ["gate", "dispatch", "ffn_fwd", "combine"] + (
-        ["combine_bwd", "gate_bwd", "ffn_bwd", "dispatch_bwd"] if wl.backward else [])
+    if args.fused:
+        phases = ["gate"] + (["dispatch"] if wl.backward else []) + ["ffn_fwd"]
+    else:
+        phases = ["gate", "dispatch", "ffn_fwd", "combine"]
+    phases += ["combine_bwd", "gate_bwd", "ffn_bwd", "dispatch_bwd"] if wl.backward else []
 
     def step(ev=None):
-        def mark(i):
+        n_mark = [0]
+
+        def mark():
             if ev is not None:
-                ev[i].record()
-        mark(0)
+                ev[n_mark[0]].record()
+            n_mark[0] += 1
+        mark()
         moe.moe_gate(sh, x, wg, bias, layer.logits, layer.probs, layer.expert, layer.gate_p, layer.slot, layer.counts,
                      layer.kept, layer.token_of_slot, layer.ws)
-        mark(1)
-        moe.moe_dispatch(sh, x, layer.token_of_slot, layer.buf)
-        mark(2)
-        moe.moe_expert_ffn_fwd(sh, layer.buf, w1, w2, layer.kept, layer.z_save, layer.hact, layer.y, layer.ws)
-        mark(3)
-        moe.moe_combine(sh, layer.y, layer.expert, layer.slot, layer.gate_p, layer.out)
-        mark(4)
+        mark()
+        if args.fused:
+            if wl.backward:      # the weight gradient reads the dispatched rows
+                moe.moe_dispatch(sh, x, layer.token_of_slot, layer.buf)
+                mark()
+            moe.moe_expert_ffn_fwd_fused(sh, None if wl.backward else x, layer.buf if wl.backward else None,
+                                         layer.token_of_slot, layer.slot, layer.gate_p, w1, w2, layer.kept,
+                                         layer.z_save, layer.hact, layer.y if wl.backward else None, layer.out,
+                                         layer.ws)
+            mark()
+        else:
+            moe.moe_dispatch(sh, x, layer.token_of_slot, layer.buf)
+            mark()
+            moe.moe_expert_ffn_fwd(sh, layer.buf, w1, w2, layer.kept, layer.z_save, layer.hact, layer.y, layer.ws)
+            mark()
+            moe.moe_combine(sh, layer.y, layer.expert, layer.slot, layer.gate_p, layer.out)
+            mark()
         if wl.backward:
             moe.moe_combine_bwd(sh, d_out, layer.y, layer.token_of_slot, layer.slot, layer.gate_p, layer.d_y,
                                 layer.d_gate_p)
-            mark(5)
+            mark()
             moe.moe_gate_bwd(sh, layer.d_gate_p, layer.probs, layer.expert, x, wg, layer.d_logits, layer.d_w_gate,
                              None, layer.ws)
-            mark(6)
+            mark()
             moe.moe_expert_ffn_bwd(sh, layer.d_y, layer.buf, layer.z_save, layer.hact, w1, w2, layer.kept,
                                    layer.d_buf, layer.d_w1, layer.d_w2, layer.ws)
-            mark(7)
+            mark()
             moe.moe_dispatch_bwd(sh, layer.d_buf, layer.expert, layer.slot, layer.d_x, layer.d_logits, wg)
-            mark(8)
+            mark()
 
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -215,7 +234,7 @@ def main() -> int:
         hbm["combine_bwd"] = 3 * n_kept * wl.hm * esz
         hbm["dispatch_bwd"] = n_kept * wl.hm * esz + wl.T * wl.hm * esz      # gate's d_x term fused in
         hbm["gate_bwd"] = wl.T * wl.hm * esz + wl.T * wl.E * 4 * 2           # d_logits, d_w_gate (reads x once)
-    hbm_frac = {p: round(b / (phase_ms[p] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) for p, b in hbm.items()}
+    hbm_frac = {p: round(b / (phase_ms[p] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) for p, b in hbm.items() if p in phase_ms}
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
@@ -254,7 +273,8 @@ def main() -> int:
                    "C": wl.C,
                    "capacity_factor": wl.capacity_factor, "n_kept": n_kept,
                    "count_min": int(counts.min()), "count_max": int(counts.max()), "seed": wl.seed,
-                   "pass": "fwd+bwd" if wl.backward else "fwd", "activation_recomputation": bool(args.recompute)},
+                   "pass": "fwd+bwd" if wl.backward else "fwd", "activation_recomputation": bool(args.recompute),
+                   "fused_permutations": bool(args.fused)},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "phase_ms": {p: round(v, 4) for p, v in phase_ms.items()},

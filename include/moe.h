@@ -154,6 +154,25 @@ moe_status_t moe_expert_ffn_fwd(const moe_shape_t *shape, const void *buf, const
 moe_status_t moe_combine(const moe_shape_t *shape, const void *y, const int32_t *expert, const int32_t *slot,
                          const float *gate_p, void *out, void *stream);
 
+/*
+ * Dispatch, expert FFN forward and combine in one call (Section 3, local halves of steps 4, 5 and 7):
+ *   out[t,:] = gate_p[t] * ( GeLU(x[t,:] w1[e_t]) w2[e_t] )   for kept tokens, 0 for dropped ones,
+ * with the two row permutations folded into the GEMMs: the first GEMM takes the rows of expert e
+ * straight from x through token_of_slot[e,:] (no dispatch buffer is written or read), and the second
+ * GEMM's epilogue writes every result row, times its token's gate probability, to that token's row of
+ * out.  bf16 only.  The results (out, and hact / z_save / y where given) are bit-identical to
+ * moe_dispatch + moe_expert_ffn_fwd + moe_combine.
+ *   x [T,h] or NULL, buf [E,C,h] or NULL: exactly one of the two (buf: rows already dispatched, as a
+ *   training step needs them anyway for the weight gradient; x: gathered, T*h*2 < 2^31),
+ *   token_of_slot [E,C], slot [T], gate_p [T], w1 [E,h,f], w2 [E,f,h], kept [E],
+ *   z_save [E,C,f] or NULL, hact [E,C,f] or NULL, y [E,C,h] or NULL (the backward needs y), out [T,h].
+ * Workspace: moe_workspace_bytes (any mode) suffices: tile plans, E*C floats, and hact when it is NULL.
+ */
+moe_status_t moe_expert_ffn_fwd_fused(const moe_shape_t *shape, const void *x, const void *buf,
+                                      const int32_t *token_of_slot, const int32_t *slot, const float *gate_p,
+                                      const void *w1, const void *w2, const int32_t *kept, void *z_save, void *hact,
+                                      void *y, void *out, void *ws, size_t ws_bytes, void *stream);
+
 /* ---- backward (end of Section 3: the same steps in reverse order) ---- */
 
 /*

@@ -139,8 +139,11 @@ struct Loader {
     int32_t kthr[CPW];    // the granule is inside K for k-tile origin k0 iff k0 < kthr
 };
 
+// `index` (KC operands only): row gx of the operand is row index[gx] of the array the resource covers
+// (negative: no such row).
 template <bool XC>
-__device__ __forceinline__ void loader_init(Loader &L, int ld, int x0, int xlim, int klim, int wave, int lane) {
+__device__ __forceinline__ void loader_init(Loader &L, int ld, int x0, int xlim, int klim, int wave, int lane,
+                                            const int32_t *index = nullptr) {
 #pragma unroll
     for (int q = 0; q < CPW; ++q) {
         const int chunk = wave * CPW + q;
@@ -154,7 +157,12 @@ __device__ __forceinline__ void loader_init(Loader &L, int ld, int x0, int xlim,
             const int row = chunk * (1024 / KC_ROW) + lane / KC_G;
             const int g = (lane % KC_G) ^ ((row >> KC_SWZ_SHIFT) & (KC_G - 1));
             const int gx = x0 + row;
-            L.off[q] = gx < xlim ? ((uint32_t)gx * ld + g * 8) * 2u : OOB;
+            if (index != nullptr) {
+                const int src = gx < xlim ? index[gx] : -1;
+                L.off[q] = src >= 0 ? ((uint32_t)src * ld + g * 8) * 2u : OOB;
+            } else {
+                L.off[q] = gx < xlim ? ((uint32_t)gx * ld + g * 8) * 2u : OOB;
+            }
             L.kthr[q] = klim - g * 8;
         }
     }
@@ -367,6 +375,8 @@ template <bool AXC, bool BXC, int EPI>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
     __shared__ __attribute__((aligned(1024))) char smem[SMEM_BYTES];
     __shared__ int s_next[8];                    // the tile fetched by thread 0: its plan entry, then its index
+    __shared__ int s_ctok[A_ROWS];               // scattered result: target row of each tile row (-1: none) ...
+    __shared__ float s_cscl[A_ROWS];             // ... and its scale
     const uint32_t smem_addr = (uint32_t)(uintptr_t)(lds_void *)smem;
     const int tid0 = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
@@ -431,10 +441,21 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
     const int m0 = blk0 * 32, n0 = nti * BN;
     const int mlim = Me < m0 + nblk * 32 ? Me : m0 + nblk * 32;     // rows [m0, mlim) are this tile's
 
-    const bf16_t *Ap = (const bf16_t *)d.A + (int64_t)e * d.strideA;
+    // gathered A (dispatch folded in): one array for all experts, rows through this expert's index slice
+    const int32_t *a_index = (!AXC && d.a_index != nullptr) ? d.a_index + (int64_t)e * d.M : nullptr;
+    const bf16_t *Ap = a_index ? (const bf16_t *)d.A : (const bf16_t *)d.A + (int64_t)e * d.strideA;
     const bf16_t *Bp = (const bf16_t *)d.B + (int64_t)e * d.strideB;
     // extent of this expert's operands in bytes (rows x row length)
-    const uint32_t a_bytes = (uint32_t)(AXC ? Ke : Me) * (uint32_t)d.lda * 2u;
+    const uint32_t a_bytes = a_index ? (uint32_t)d.a_rows * (uint32_t)d.lda * 2u
+                                     : (uint32_t)(AXC ? Ke : Me) * (uint32_t)d.lda * 2u;
+    // scattered result (combine folded in): target row and scale of each of the tile's rows, through LDS
+    const bool scatter = EPI == EPI_STORE && d.c_index != nullptr;
+    if (scatter && tid < A_ROWS) {
+        const int gm = m0 + tid;
+        const bool ok = gm < mlim;
+        s_ctok[tid] = ok ? d.c_index[(int64_t)e * d.M + gm] : -1;
+        s_cscl[tid] = ok ? d.c_scale[(int64_t)e * d.M + gm] : 0.f;
+    }
     const uint32_t b_bytes = (uint32_t)(BXC ? Ke : d.N) * (uint32_t)d.ldb * 2u;
     const i32x4 A = make_rsrc(Ap, a_bytes), B = make_rsrc(Bp, b_bytes);
 
@@ -458,7 +479,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
     // (a0/b0, a1/b1), all read in the memory phase that precedes the tile's 16 MFMAs.
     bf16x8 a0[4], b0[2], a1[4], b1[2], ax0, ax1, bx0, bx1;
     Loader la, lb;
-    loader_init<AXC>(la, d.lda, m0, mlim, Ke, wave, lane);
+    loader_init<AXC>(la, d.lda, m0, mlim, Ke, wave, lane, a_index);
     loader_init<BXC>(lb, d.ldb, n0, d.N, Ke, wave, lane);
     // tall tile: the two 1 KB chunks of rows 256..287 are loaded by waves 0 and 5 (one wave of each
     // ping-pong group, on different SIMDs), which therefore have 5 loads per k-tile in flight
@@ -470,7 +491,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
         const int row = 256 + 16 * xw + (lane >> 2);
         const int g = (lane & 3) ^ ((row >> KC_SWZ_SHIFT) & (KC_G - 1));
         const int gx = m0 + row;
-        offx = gx < mlim ? ((uint32_t)gx * d.lda + g * 8) * 2u : OOB;
+        if (a_index != nullptr) {
+            const int src = gx < mlim ? a_index[gx] : -1;
+            offx = src >= 0 ? ((uint32_t)src * d.lda + g * 8) * 2u : OOB;
+        } else {
+            offx = gx < mlim ? ((uint32_t)gx * d.lda + g * 8) * 2u : OOB;
+        }
         kthrx = Ke - g * 8;
     }
     // 32-row blocks of this wave that hold valid rows (4 except in a last, partial m-tile)
@@ -688,7 +714,34 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
     };
     if (EPI == EPI_STORE) {
         for_each_quad([&](bf16_t *pos, const f32x4 &v) { put4(pos, v); });
-        flush(C);
+        if (!scatter) {
+            flush(C);
+        } else {
+            // result row (if C is given) and the scaled row at its target: the staged bf16 value times the
+            // scale, rounded again -- exactly what a separate combine pass over C would produce
+            bf16_t *S = (bf16_t *)d.C_scatter;
+            const bool keep = d.C != nullptr;
+            __syncthreads();
+            auto spass = [&](int p) {
+                const int row = (tid >> 5) + 16 * p, gm = m0 + row, gn = n0 + (tid & 31) * 8;
+                const u32x4 v = *(const u32x4 *)(st + row * CLD + (tid & 31) * 8);
+                const int trg = s_ctok[row];
+                const float scl = s_cscl[row];
+                if (gm < mlim && gn < d.N) {
+                    if (keep) *(u32x4 *)(C + (int64_t)gm * d.ldc + gn) = v;
+                    if (trg >= 0) {
+                        const bf16x8 b = __builtin_bit_cast(bf16x8, v);
+                        bf16x8 o;
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) o[q] = (bf16_t)((float)b[q] * scl);
+                        *(u32x4 *)(S + (int64_t)trg * d.ldc + gn) = __builtin_bit_cast(u32x4, o);
+                    }
+                }
+            };
+#pragma unroll
+            for (int p = 0; p < 16; ++p) spass(p);
+            if (tall) { spass(16); spass(17); }
+        }
     } else if (EPI == EPI_GELU) {
         // The activation is a compile-time constant inside (one branch per tile, not per element).
         auto gelu_stage = [&](auto actc) __attribute__((always_inline)) {

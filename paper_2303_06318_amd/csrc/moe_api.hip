@@ -36,6 +36,8 @@ moe_status_t run_dispatch_bwd(const moe_shape_t *, const void *, const int32_t *
                               hipStream_t);
 moe_status_t run_combine(const moe_shape_t *, const void *, const int32_t *, const int32_t *, const float *, void *,
                          hipStream_t);
+moe_status_t run_combine_prep(const moe_shape_t *, const int32_t *, const int32_t *, const float *, float *, void *,
+                              hipStream_t);
 moe_status_t run_combine_bwd(const moe_shape_t *, const void *, const void *, const int32_t *, const int32_t *,
                              const float *, void *, float *, hipStream_t);
 moe_status_t run_gate_bwd(const moe_shape_t *, const float *, const float *, const int32_t *, const void *,
@@ -163,8 +165,10 @@ static size_t ffn_plan_bytes(const moe_shape_t *sh, int first, int last) {
 // Workspace layouts of the FFN entry points ([E,C,f] arrays first, each rounded to 256 bytes, plans last):
 //   forward:   [hact if the caller keeps none][plans of GEMM1, GEMM2]
 //   backward:  [d_z][hact, GeLU'(z) if recomputed][plan of GEMM1 if recomputed][plans of the four backward GEMMs]
-static size_t ffn_fwd_ws_bytes(const moe_shape_t *sh, bool own_hact) {
-    return (own_hact ? dz_bytes(sh) : 0) + ffn_plan_bytes(sh, G_FWD1, G_FWD2);
+static size_t slot_scale_bytes(const moe_shape_t *sh) { return round256((size_t)sh->E * sh->C * 4); }
+//   fused forward (dispatch and combine folded in):  [hact if the caller keeps none][scale of every slot][plans]
+static size_t ffn_fwd_ws_bytes(const moe_shape_t *sh, bool own_hact, bool fused = false) {
+    return (own_hact ? dz_bytes(sh) : 0) + (fused ? slot_scale_bytes(sh) : 0) + ffn_plan_bytes(sh, G_FWD1, G_FWD2);
 }
 static size_t ffn_bwd_ws_bytes(const moe_shape_t *sh, bool recompute) {
     return dz_bytes(sh) * (recompute ? 3 : 1) + (recompute ? ffn_plan_bytes(sh, G_FWD1, G_FWD1) : 0) +
@@ -174,7 +178,7 @@ static size_t ffn_bwd_ws_bytes(const moe_shape_t *sh, bool recompute) {
 static size_t ws_bytes_checked(const moe_shape_t *sh, int for_backward) {
     const bool recompute = for_backward == 2;
     size_t need = gate_ws_bytes(sh);
-    if (ffn_fwd_ws_bytes(sh, recompute) > need) need = ffn_fwd_ws_bytes(sh, recompute);
+    if (ffn_fwd_ws_bytes(sh, recompute, true) > need) need = ffn_fwd_ws_bytes(sh, recompute, true);
     if (!for_backward) return need;
     if (ffn_bwd_ws_bytes(sh, recompute) > need) need = ffn_bwd_ws_bytes(sh, recompute);
     if (round256(gate_bwd_ws_bytes(sh)) > need) need = round256(gate_bwd_ws_bytes(sh));
@@ -321,6 +325,63 @@ moe_status_t moe_expert_ffn_fwd(const moe_shape_t *shape, const void *buf, const
     }
     for (int i = 0; i < 2; ++i)
         if ((st = bf ? launch_gemm_bf16(g[i], hs) : launch_gemm_f32(g[i], hs)) != MOE_OK) return st;
+    return MOE_OK;
+}
+
+moe_status_t moe_expert_ffn_fwd_fused(const moe_shape_t *shape, const void *x, const void *buf,
+                                      const int32_t *token_of_slot, const int32_t *slot, const float *gate_p,
+                                      const void *w1, const void *w2, const int32_t *kept, void *z_save, void *hact,
+                                      void *y, void *out, void *ws, size_t ws_bytes, void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if (shape->dtype != MOE_BF16) {
+        set_error("moe_expert_ffn_fwd_fused: bf16 storage only (use moe_dispatch, moe_expert_ffn_fwd, moe_combine)");
+        return MOE_ERR_UNSUPPORTED;
+    }
+    OPTIONAL_PTR(x);
+    OPTIONAL_PTR(buf);
+    if ((x == nullptr) == (buf == nullptr)) {
+        set_error("moe_expert_ffn_fwd_fused: give either x (rows are gathered) or buf (already dispatched)");
+        return MOE_ERR_INVALID_ARG;
+    }
+    REQUIRE_PTR(token_of_slot);
+    REQUIRE_PTR(slot);
+    REQUIRE_PTR(gate_p);
+    REQUIRE_PTR(w1);
+    REQUIRE_PTR(w2);
+    REQUIRE_PTR(kept);
+    OPTIONAL_PTR(z_save);
+    OPTIONAL_PTR(hact);
+    OPTIONAL_PTR(y);
+    REQUIRE_PTR(out);
+    const moe_shape_t &s = *shape;
+    if (x != nullptr && (double)s.T * s.h * 2.0 >= 2147483648.0) {
+        set_error("moe_expert_ffn_fwd_fused: T*h*2 = %.0f bytes of x exceed the 2 GiB a gathered operand can span",
+                  (double)s.T * s.h * 2.0);
+        return MOE_ERR_UNSUPPORTED;
+    }
+    const bool own_hact = hact == nullptr;
+    st = check_ws("moe_expert_ffn_fwd_fused", ws, ws_bytes, ffn_fwd_ws_bytes(shape, own_hact, true));
+    if (st != MOE_OK) return st;
+    hipStream_t hs = (hipStream_t)stream;
+    char *w = (char *)ws;
+    if (own_hact) { hact = w; w += dz_bytes(shape); }
+    float *scale_of_slot = (float *)w;
+    w += slot_scale_bytes(shape);
+    GemmDesc g[2] = {ffn_gemm(s, G_FWD1), ffn_gemm(s, G_FWD2)};
+    g[0].B = w1; g[0].C = hact; g[0].C2 = z_save; g[0].kept = kept;
+    if (buf != nullptr) {
+        g[0].A = buf;
+    } else {
+        g[0].A = x; g[0].a_index = token_of_slot; g[0].a_rows = s.T;
+    }
+    g[1].A = hact; g[1].B = w2; g[1].C = y; g[1].kept = kept;
+    g[1].c_index = token_of_slot; g[1].c_scale = scale_of_slot; g[1].C_scatter = out;
+    for (int i = 0; i < 2; ++i) { g[i].plan = w; w += gemm_bf16_plan_bytes(g[i]); }
+    if ((st = launch_gemm_bf16_plans(g, 2, hs)) != MOE_OK) return st;
+    if ((st = run_combine_prep(shape, token_of_slot, slot, gate_p, scale_of_slot, out, hs)) != MOE_OK) return st;
+    for (int i = 0; i < 2; ++i)
+        if ((st = launch_gemm_bf16(g[i], hs)) != MOE_OK) return st;
     return MOE_OK;
 }
 

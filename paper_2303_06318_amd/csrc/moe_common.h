@@ -58,6 +58,17 @@ struct GemmDesc {
     int32_t E;
     int32_t a_xc, b_xc, rows_from_kept, epi, act;
     void *plan;       // bf16 path: device buffer of gemm_bf16_plan_bytes() bytes holding this launch's tile plan
+    // bf16 path, optional fusions of the row permutations (rows_from_kept GEMMs with a KC A operand):
+    //   a_index != null: row r of expert e's A operand is row a_index[e*M + r] of the one [a_rows, lda]
+    //   array A (dispatch folded into the operand load; strideA is unused);
+    //   c_index != null (EPI_STORE): row r of expert e's result, times c_scale[e*M + r] and rounded again, is
+    //   also written to row c_index[e*M + r] of C_scatter [*, ldc] (combine folded into the epilogue); C may
+    //   then be null.
+    const int32_t *a_index;
+    int64_t a_rows;
+    const int32_t *c_index;
+    const float *c_scale;
+    void *C_scatter;
 };
 
 moe_status_t launch_gemm_f32(const GemmDesc &d, hipStream_t s);

@@ -126,6 +126,28 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const u32x4 *d_out, co
     }
 }
 
+// Preparation of the combine that is folded into the second GEMM's epilogue: the scale of every
+// buffer row (gate probability of the token in that slot, 0 for an empty slot), and zero rows of `out`
+// for dropped tokens, which no buffer row maps to.  Blocks [0, scale_blocks) do the first, one block
+// per token the second.
+__global__ __launch_bounds__(256) void combine_prep_kernel(const int32_t *token_of_slot, const int32_t *slot,
+                                                            const float *gate_p, float *scale_of_slot, u32x4 *out,
+                                                            int64_t rows, int64_t Tn, int words, int scale_blocks) {
+    if ((int)blockIdx.x < scale_blocks) {
+        const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+        if (r < rows) {
+            const int tok = token_of_slot[r];
+            scale_of_slot[r] = tok >= 0 ? gate_p[tok] : 0.f;
+        }
+        return;
+    }
+    const int64_t t = (int64_t)blockIdx.x - scale_blocks;
+    if (t >= Tn || slot[t] >= 0) return;
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    u32x4 *o = out + t * words;
+    for (int i = threadIdx.x; i < words; i += 256) o[i] = z;
+}
+
 // ------------------------------------------------------------------ host side
 static unsigned row_grid(int64_t rows) { return (unsigned)(rows < 1048576 ? rows : 1048576); }
 
@@ -159,6 +181,17 @@ moe_status_t run_combine(const moe_shape_t *sh, const void *y, const int32_t *ex
         hipLaunchKernelGGL(combine_kernel<float>, dim3(row_grid(sh->T)), dim3(256), 0, s, (const u32x4 *)y, expert,
                            slot, gate_p, (u32x4 *)out, sh->T, sh->C, words);
     return check_launch("combine");
+}
+
+moe_status_t run_combine_prep(const moe_shape_t *sh, const int32_t *token_of_slot, const int32_t *slot,
+                              const float *gate_p, float *scale_of_slot, void *out, hipStream_t s) {
+    const int esz = sh->dtype == MOE_BF16 ? 2 : 4;
+    const int words = sh->h * esz / 16;
+    const int64_t rows = (int64_t)sh->E * sh->C;
+    const int scale_blocks = (int)((rows + 255) / 256);
+    hipLaunchKernelGGL(combine_prep_kernel, dim3((unsigned)(scale_blocks + sh->T)), dim3(256), 0, s, token_of_slot, slot,
+                       gate_p, scale_of_slot, (u32x4 *)out, rows, sh->T, words, scale_blocks);
+    return check_launch("combine_prep");
 }
 
 moe_status_t run_combine_bwd(const moe_shape_t *sh, const void *d_out, const void *y, const int32_t *token_of_slot,

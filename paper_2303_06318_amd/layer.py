@@ -62,8 +62,18 @@ class MoeLayer:
         moe.moe_gate(self.shape, x, w_gate, logit_bias, self.logits, self.probs, self.expert, self.gate_p, self.slot,
                      self.counts, self.kept, self.token_of_slot, self.ws)
 
-    def forward(self, x, w_gate, w1, w2, logit_bias=None, logits_in=None):
+    def forward(self, x, w_gate, w1, w2, logit_bias=None, logits_in=None, fused=False):
+        """fused=True: dispatch and combine folded into the expert GEMMs (bf16).  A layer that will run a
+        backward still dispatches (the weight gradient reads buf); a forward-only layer gathers from x."""
         self.gate(x, w_gate, logit_bias, logits_in)
+        if fused:
+            if self.backward_enabled:
+                moe.moe_dispatch(self.shape, x, self.token_of_slot, self.buf)
+            moe.moe_expert_ffn_fwd_fused(self.shape, None if self.backward_enabled else x,
+                                         self.buf if self.backward_enabled else None, self.token_of_slot, self.slot,
+                                         self.gate_p, w1, w2, self.kept, self.z_save, self.hact,
+                                         self.y if self.backward_enabled else None, self.out, self.ws)
+            return self.out
         moe.moe_dispatch(self.shape, x, self.token_of_slot, self.buf)
         moe.moe_expert_ffn_fwd(self.shape, self.buf, w1, w2, self.kept, self.z_save, self.hact, self.y, self.ws)
         moe.moe_combine(self.shape, self.y, self.expert, self.slot, self.gate_p, self.out)

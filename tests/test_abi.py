@@ -126,6 +126,27 @@ def test_recompute_mode_arguments():
     assert st == moe.MOE_ERR_WORKSPACE_TOO_SMALL
 
 
+def test_fused_forward_arguments():
+    a = 4096
+    L = moe.lib()
+    p = C.c_void_p(a)
+    sh = moe.make_shape(1024, 512, 8, 512, 128)
+    big = 1 << 40
+    # both x and buf, or neither
+    assert L.moe_expert_ffn_fwd_fused(C.byref(sh), p, p, p, p, p, p, p, p, None, None, None, p, p, big, None) == moe.MOE_ERR_INVALID_ARG
+    assert L.moe_expert_ffn_fwd_fused(C.byref(sh), None, None, p, p, p, p, p, p, None, None, None, p, p, big, None) == moe.MOE_ERR_INVALID_ARG
+    assert b"either x" in L.moe_last_error()
+    # fp32 storage is not served by the fused call
+    sh32 = moe.make_shape(1024, 512, 8, 512, 128, moe.MOE_F32)
+    assert L.moe_expert_ffn_fwd_fused(C.byref(sh32), p, None, p, p, p, p, p, p, None, None, None, p, p, big, None) == moe.MOE_ERR_UNSUPPORTED
+    # x too large for a gathered operand
+    shb = moe.make_shape(1 << 19, 4096, 8, 512, 1 << 16)
+    assert L.moe_expert_ffn_fwd_fused(C.byref(shb), p, None, p, p, p, p, p, p, None, None, None, p, p, big, None) == moe.MOE_ERR_UNSUPPORTED
+    assert b"2 GiB" in L.moe_last_error()
+    # workspace
+    assert L.moe_expert_ffn_fwd_fused(C.byref(sh), p, None, p, p, p, p, p, p, None, None, None, p, p, 64, None) == moe.MOE_ERR_WORKSPACE_TOO_SMALL
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(moe, "_lib", None)
     monkeypatch.setattr(moe, "LIB_PATH", "/nonexistent/libmoe_ted.so")

@@ -304,3 +304,39 @@ def test_activation_recomputation_gives_identical_bits(orc, name):
     esz = 2 if wl.dtype == "bf16" else 4
     extra = moe.moe_workspace_bytes(sh, 2) - moe.moe_workspace_bytes(sh, 1)
     assert 0 < extra <= 2 * (wl.E * wl.C * wl.f * esz + 256) + 65536
+
+
+@pytest.mark.parametrize("name", ["cfg2_small", "cfg3_small", "cfg4_small", "cfg5_small", "bf16_one_expert",
+                                  "bf16_bwd_E200", "bf16_bwd_9blocks", "bf16_bwd_18blocks"])
+def test_fused_forward_gives_identical_bits(orc, name):
+    """Dispatch folded into GEMM1's operand load and combine into GEMM2's epilogue: out (and hact, z_save, y
+    where kept) must equal the three-call path bit for bit; the forward-only form writes no dispatch buffer."""
+    from gpu_util import poison
+    wl = CASES[name]
+    inp = synth.make_inputs(wl)
+    dev = DevInputs(inp)
+    ref = make_layer(wl, backward=True)
+    ref.forward(dev.x, dev.wg, dev.w1, dev.w2, logit_bias=dev.bias)
+    torch.cuda.synchronize()
+    kept = host(ref.kept)
+    out_ref = host(ref.out)
+    # forward-only: gathers from x, keeps neither buf nor y
+    fwd = make_layer(wl, backward=False)
+    fwd.forward(dev.x, dev.wg, dev.w1, dev.w2, logit_bias=dev.bias, fused=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(fwd.out).view(np.uint32), out_ref.view(np.uint32))
+    assert np.array_equal(kept_rows(host(fwd.hact), kept), kept_rows(host(ref.hact), kept))
+    assert fwd.buf.view(torch.uint8).min().item() == 0xFF          # still the poison pattern: never written
+    assert fwd.y.view(torch.uint8).min().item() == 0xFF
+    if (host(ref.slot) < 0).any():
+        assert not out_ref[host(ref.slot) < 0].any()
+    # training form: dispatched rows given, y / hact / z_save kept for the backward
+    trn = make_layer(wl, backward=True)
+    trn.forward(dev.x, dev.wg, dev.w1, dev.w2, logit_bias=dev.bias, fused=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(trn.out).view(np.uint32), out_ref.view(np.uint32))
+    for a, b in ((trn.hact, ref.hact), (trn.z_save, ref.z_save), (trn.y, ref.y), (trn.buf, ref.buf)):
+        assert np.array_equal(kept_rows(host(a), kept), kept_rows(host(b), kept))
+    # and the oracle, once more, on the fused output
+    fw = orc.layer_forward(inp.x, inp.wg, inp.w1, inp.w2, wl.C, logits=host(ref.logits))
+    assert relfro(host(fwd.out), fw["out"]) <= tol(wl)
