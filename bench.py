@@ -29,7 +29,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per GEMM launch (average over the launches of a step) from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs, scaled by what the same counters read for a plain 1 GiB copy
 # (profiles/gemm_bf16_cfg5_fwdbwd.md, section 2); keyed by workload name, None where not measured.
-MEASURED_GEMM_TRAFFIC_BYTES = {"cfg5_6p7b_tp4_fwdbwd": 1.228e9}
+MEASURED_GEMM_TRAFFIC_BYTES = {"cfg5_6p7b_tp4_fwdbwd": 1.209e9}
 
 
 def bench_optimizer(args, wl, layer, w1, w2):
