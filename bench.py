@@ -94,7 +94,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg5_6p7b_tp4_fwdbwd")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=768)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (known size) so that HBM counters can be scaled")
     ap.add_argument("--optimizer", action="store_true",

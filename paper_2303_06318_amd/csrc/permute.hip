@@ -128,8 +128,9 @@ __global__ __launch_bounds__(256) void combine_bwd_kernel(const u32x4 *d_out, co
 
 // Preparation of the combine that is folded into the second GEMM's epilogue: the scale of every
 // buffer row (gate probability of the token in that slot, 0 for an empty slot), and zero rows of `out`
-// for dropped tokens, which no buffer row maps to.  Blocks [0, scale_blocks) do the first, one block
-// per token the second.
+// for dropped tokens, which no buffer row maps to.  Blocks [0, scale_blocks) do the first; each of the
+// others looks at 16 tokens, 4 per wave, and a wave clears the rows of its dropped ones.
+constexpr int PREP_TOKENS = 16;
 __global__ __launch_bounds__(256) void combine_prep_kernel(const int32_t *token_of_slot, const int32_t *slot,
                                                             const float *gate_p, float *scale_of_slot, u32x4 *out,
                                                             int64_t rows, int64_t Tn, int words, int scale_blocks) {
@@ -141,11 +142,15 @@ __global__ __launch_bounds__(256) void combine_prep_kernel(const int32_t *token_
         }
         return;
     }
-    const int64_t t = (int64_t)blockIdx.x - scale_blocks;
-    if (t >= Tn || slot[t] >= 0) return;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t t0 = ((int64_t)blockIdx.x - scale_blocks) * PREP_TOKENS + wave * (PREP_TOKENS / 4);
     const u32x4 z = {0u, 0u, 0u, 0u};
-    u32x4 *o = out + t * words;
-    for (int i = threadIdx.x; i < words; i += 256) o[i] = z;
+    for (int i = 0; i < PREP_TOKENS / 4; ++i) {
+        const int64_t t = t0 + i;
+        if (t >= Tn || slot[t] >= 0) continue;
+        u32x4 *o = out + t * words;
+        for (int w = lane; w < words; w += 64) o[w] = z;
+    }
 }
 
 // ------------------------------------------------------------------ host side
@@ -189,7 +194,8 @@ moe_status_t run_combine_prep(const moe_shape_t *sh, const int32_t *token_of_slo
     const int words = sh->h * esz / 16;
     const int64_t rows = (int64_t)sh->E * sh->C;
     const int scale_blocks = (int)((rows + 255) / 256);
-    hipLaunchKernelGGL(combine_prep_kernel, dim3((unsigned)(scale_blocks + sh->T)), dim3(256), 0, s, token_of_slot, slot,
+    const int64_t token_blocks = (sh->T + PREP_TOKENS - 1) / PREP_TOKENS;
+    hipLaunchKernelGGL(combine_prep_kernel, dim3((unsigned)(scale_blocks + token_blocks)), dim3(256), 0, s, token_of_slot, slot,
                        gate_p, scale_of_slot, (u32x4 *)out, rows, sh->T, words, scale_blocks);
     return check_launch("combine_prep");
 }
