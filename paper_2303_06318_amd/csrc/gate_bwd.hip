@@ -1,4 +1,5 @@
 // Gate backward: d_logits from the softmax Jacobian, d_w_gate = X^T d_logits, d_x += d_logits w_gate^T.
+#include <cstdlib>
 #include "moe_common.h"
 
 namespace moe {
@@ -391,7 +392,7 @@ __global__ __launch_bounds__(256) void gate_dx_mfma_kernel(const float *w_gate, 
         srow[tid] = r;
     }
     __syncthreads();
-    // the 4 token rows of a thread (16 bytes each), requested one tile ahead
+    // the 4 token rows of a thread (16 bytes each), requested one tile ahead, in two alternating sets
     u32x4 raw[4], nxt[4];
     auto load_rows = [&](int it, u32x4(&dst)[4]) {
         const int64_t tb = t_first + (int64_t)it * TT;
@@ -409,36 +410,36 @@ __global__ __launch_bounds__(256) void gate_dx_mfma_kernel(const float *w_gate, 
             }
         }
     };
-    load_rows(0, nxt);
-    for (int it = 0; it < tiles_per_wg; ++it) {
+    // One tile: MFMAs into G, then every thread adds its 4 row pieces and writes them.  The row pieces are
+    // waited for only here, at their use, and the next tile's d_logits are requested as soon as this tile's
+    // have been split, so both have most of a tile's time to arrive.
+    auto tile = [&](int it, const u32x4(&rows)[4]) {
         const int64_t tb = t_first + (int64_t)it * TT;
-        if (tb >= T) break;
         if (it > 0) __syncthreads();                // G of the previous tile has been read
+        bf16x8 ah[KB], al[KB];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) raw[u] = nxt[u];
-        load_rows(it + 1, nxt);
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const bf16_t hq = f32_to_bf16(araw[kb][q]);
+                ah[kb][q] = hq;
+                al[kb][q] = f32_to_bf16(araw[kb][q] - bf16_to_f32(hq));
+            }
+        if (it + 1 < tiles_per_wg && tb + TT < T) load_a(tb + TT);
         f32x16 acc[2];
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-            bf16x8 ah, al;
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const bf16_t hq = f32_to_bf16(araw[kb][q]);
-                ah[q] = hq;
-                al[q] = f32_to_bf16(araw[kb][q] - bf16_to_f32(hq));
-            }
+        for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 // operands swapped: the lane ends up with token row lane % 32 and 4 consecutive columns per quad
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh[j][kb], ah, acc[j], 0, 0, 0);
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bl[j][kb], ah, acc[j], 0, 0, 0);
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh[j][kb], al, acc[j], 0, 0, 0);
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh[j][kb], ah[kb], acc[j], 0, 0, 0);
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bl[j][kb], ah[kb], acc[j], 0, 0, 0);
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh[j][kb], al[kb], acc[j], 0, 0, 0);
             }
-        }
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -446,14 +447,13 @@ __global__ __launch_bounds__(256) void gate_dx_mfma_kernel(const float *w_gate, 
                 const f32x4 v = {acc[j][vq * 4], acc[j][vq * 4 + 1], acc[j][vq * 4 + 2], acc[j][vq * 4 + 3]};
                 *(f32x4 *)&G[lane & 31][wave * 64 + j * 32 + vq * 8 + (lane >> 5) * 4] = v;
             }
-        if (it + 1 < tiles_per_wg && tb + TT < T) load_a(tb + TT);
         __syncthreads();
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int tt = (tid >> 5) + 8 * u;
             if (!cin || tb + tt >= T) continue;
             const f32x4 g0 = *(const f32x4 *)&G[tt][c8], g1 = *(const f32x4 *)&G[tt][c8 + 4];
-            const bf16x8 b = __builtin_bit_cast(bf16x8, raw[u]);
+            const bf16x8 b = __builtin_bit_cast(bf16x8, rows[u]);
             bf16x8 o;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -462,6 +462,16 @@ __global__ __launch_bounds__(256) void gate_dx_mfma_kernel(const float *w_gate, 
             }
             *(bf16x8 *)(d_x + (tb + tt) * h + c0 + c8) = o;
         }
+    };
+    // number of this workgroup's tiles that hold tokens (uniform)
+    int ntile = tiles_per_wg;
+    if (t_first + (int64_t)ntile * TT > T) ntile = (int)((T - t_first + TT - 1) / TT);
+    load_rows(0, raw);
+    for (int it = 0; it < ntile; it += 2) {
+        load_rows(it + 1, nxt);
+        tile(it, raw);
+        load_rows(it + 2, raw);
+        if (it + 1 < ntile) tile(it + 1, nxt);
     }
 }
 
@@ -540,7 +550,7 @@ static void launch_dx(const moe_shape_t *sh, const float *w_gate, const float *d
 
 static void launch_dx_mfma(const moe_shape_t *sh, const float *w_gate, const float *d_logits, void *d_x, hipStream_t s,
                            const void *d_buf = nullptr, const int32_t *expert = nullptr, const int32_t *slot = nullptr) {
-    const int tiles_per_wg = 8;                     // at most 8: the kernel keeps one gather row per thread
+    const int tiles_per_wg = 8;                     // at most 8: the kernel keeps one gather row per thread (4 to 8 are equally fast)
     dim3 grid((unsigned)((sh->h + 255) / 256), (unsigned)((sh->T + 32 * tiles_per_wg - 1) / (32 * tiles_per_wg)));
 #define MOE_DX_MFMA(KB)                                                                                                  \
     hipLaunchKernelGGL((gate_dx_mfma_kernel<KB>), grid, dim3(256), 0, s, w_gate, d_logits, (bf16_t *)d_x, sh->T, sh->h, \
