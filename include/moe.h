@@ -32,7 +32,9 @@
  *    stream, created once per device on first use and kept until the process ends;
  *    that stream starts behind an event of `stream` and `stream` waits for its last
  *    event before the call's work is complete, so the caller still orders everything
- *    on `stream` alone.
+ *    on `stream` alone.  That stream and its events are shared by all calls on a device:
+ *    calling moe_expert_ffn_bwd from several host threads at once on one device is not
+ *    supported (set MOE_TED_SERIAL=1 before the first call to keep everything on `stream`).
  *  - `dtype` is the storage type of x, buffers, expert weights and their
  *    gradients: MOE_BF16 (fp32 accumulation on MFMA) or MOE_F32.  The gate
  *    (w_gate, logits, probs, gate_p and their gradients) is always fp32.
