@@ -42,10 +42,10 @@ class DevInputs:
         self.bias = None if inp.logit_bias is None else torch.from_numpy(inp.logit_bias).cuda()
 
 
-def make_layer(wl: synth.Workload, backward=None, act=moe.MOE_GELU_ERF) -> MoeLayer:
+def make_layer(wl: synth.Workload, backward=None, act=moe.MOE_GELU_ERF, **modes) -> MoeLayer:
     dt = moe.MOE_BF16 if wl.dtype == "bf16" else moe.MOE_F32
     bw = wl.backward if backward is None else backward
-    layer = MoeLayer(wl.T, wl.h, wl.E, wl.f, wl.C, dt, act, backward=bw)
+    layer = MoeLayer(wl.T, wl.h, wl.E, wl.f, wl.C, dt, act, backward=bw, **modes)
     poison(layer)
     return layer
 

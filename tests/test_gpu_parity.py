@@ -273,6 +273,17 @@ def test_random_shapes(orc, wl):
     assert relfro(host(layer.d_w2), bw["dW2"]) <= t
     assert relfro(host(layer.d_x), bw["dX"]) <= t
     assert relfro(host(layer.d_w_gate), bw["dWg"]) <= t
+    # the same shape through the fused forward (gathered A, scattered result) and the recomputing backward:
+    # bit-identical to the run above
+    alt = make_layer(wl, backward=True, recompute=True)
+    alt.gate(dev.x, dev.wg, dev.bias)
+    moe.moe_expert_ffn_fwd_fused(alt.shape, dev.x, None, alt.token_of_slot, alt.slot, alt.gate_p, dev.w1, dev.w2,
+                                 alt.kept, None, None, alt.y, alt.out, alt.ws)
+    moe.moe_dispatch(alt.shape, dev.x, alt.token_of_slot, alt.buf)      # the backward's weight gradient reads buf
+    alt.backward(dev.d_out, dev.x, dev.wg, dev.w1, dev.w2)
+    torch.cuda.synchronize()
+    for a, b in ((alt.out, layer.out), (alt.d_x, layer.d_x), (alt.d_w1, layer.d_w1), (alt.d_w2, layer.d_w2)):
+        assert np.array_equal(host(a).view(np.uint32), host(b).view(np.uint32))
 
 
 @pytest.mark.parametrize("name", ["cfg5_small", "f32_bwd", "bf16_bwd_9blocks", "bf16_bwd_E64"])
