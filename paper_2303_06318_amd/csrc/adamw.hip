@@ -9,8 +9,9 @@
 //           exists at all and the whole group is one launch.
 // Both produce the same bits: the staged value is exactly the fp32 number the fused path holds in a
 // register.  The kernels are plain streaming kernels, bound by HBM: per parameter 14 bytes are read
-// (2 gradient + 4 master + 4 + 4 moments) and 14 written (bf16 storage; the staged path adds a 4-byte
-// write and a 4-byte read of the staging tile, which a tile of a few MB keeps in L2 / MALL).
+// (2 gradient + 4 master + 4 + 4 moments) and 14 written (bf16 storage); the staged path adds a 4-byte
+// write and a 4-byte read of the staging tile, which the memory counters show going to memory and back
+// even for a tile of 7 MB (the L2 caches are per XCD, and the reader is in general on another XCD).
 #include "moe_common.h"
 
 namespace moe {
