@@ -33,6 +33,11 @@ CASES = {
 }
 
 
+def bits(a):
+    """Bit pattern view for exact comparisons of float arrays."""
+    return a.view(np.uint32) if a.dtype == np.float32 else a
+
+
 def run_forward(wl, act=moe.MOE_GELU_ERF, backward=None):
     inp = synth.make_inputs(wl)
     dev = DevInputs(inp)
@@ -351,3 +356,40 @@ def test_fused_forward_gives_identical_bits(orc, name):
     # and the oracle, once more, on the fused output
     fw = orc.layer_forward(inp.x, inp.wg, inp.w1, inp.w2, wl.C, logits=host(ref.logits))
     assert relfro(host(fwd.out), fw["out"]) <= tol(wl)
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg5_small"])
+def test_step_is_graph_capturable_and_replays_identically(name):
+    """The whole forward + backward (side stream of the backward included) is captured into a HIP graph;
+    three replays, with eager work and synchronisations between them, must reproduce the eager results."""
+    wl = synth.scaled(CASES[name], backward=True)
+    inp = synth.make_inputs(wl)
+    dev = DevInputs(inp)
+    layer = make_layer(wl, backward=True)
+
+    def step():
+        layer.forward(dev.x, dev.wg, dev.w1, dev.w2, logit_bias=dev.bias)
+        layer.backward(dev.d_out, dev.x, dev.wg, dev.w1, dev.w2)
+
+    step()
+    torch.cuda.synchronize()
+    outs = (layer.out, layer.d_x, layer.d_w1, layer.d_w2, layer.d_w_gate)
+    ref = [host(t).copy() for t in outs]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # warm-up on a non-default stream, as capture requires
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for _ in range(3):
+        for t in outs:
+            t.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(ref, [host(t) for t in outs]):
+            assert np.array_equal(bits(a), bits(b))
+        assert torch.isfinite(torch.randn(4096, device="cuda").sum()).item()      # eager work between replays
