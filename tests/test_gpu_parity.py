@@ -28,6 +28,9 @@ CASES = {
     "bf16_bwd_E200": synth.scaled(W["cfg5_6p7b_tp4_fwdbwd"], T=2100, h=136, f=72, E=200, capacity_factor=2.0),
     # full experts hold 275 rows = 9 MFMA blocks (one 9-block GEMM tile), the others a ragged 6-9 blocks
     "bf16_bwd_9blocks": synth.scaled(W["cfg5_6p7b_tp4_fwdbwd"], T=1100, h=264, f=328, E=4, capacity_factor=1.0),
+    # the largest expert count the library takes, with capacity 1: every expert keeps at most one token,
+    # most tokens are dropped, some experts stay empty
+    "bf16_E256_C1": synth.scaled(W["cfg5_6p7b_tp4_fwdbwd"], T=300, h=72, f=40, E=256, capacity_factor=0.8),
     # 560 rows = 18 blocks = two 9-block tiles; 600 rows = 19 blocks = 7 + 6 + 6
     "bf16_bwd_18blocks": synth.scaled(W["cfg5_6p7b_tp4_fwdbwd"], T=1120, h=136, f=264, E=2, capacity_factor=1.0),
 }
@@ -95,7 +98,7 @@ def test_forward_parity(orc, name):
 
 
 @pytest.mark.parametrize("name", ["cfg5_small", "f32_bwd", "bf16_one_expert", "bf16_bwd_E64", "bf16_bwd_E200",
-                                  "bf16_bwd_9blocks", "bf16_bwd_18blocks"])
+                                  "bf16_E256_C1", "bf16_bwd_9blocks", "bf16_bwd_18blocks"])
 @pytest.mark.parametrize("act", [moe.MOE_GELU_ERF, moe.MOE_GELU_TANH])
 def test_backward_parity(orc, name, act):
     wl = CASES[name]
@@ -323,7 +326,7 @@ def test_activation_recomputation_gives_identical_bits(orc, name):
 
 
 @pytest.mark.parametrize("name", ["cfg2_small", "cfg3_small", "cfg4_small", "cfg5_small", "bf16_one_expert",
-                                  "bf16_bwd_E200", "bf16_bwd_9blocks", "bf16_bwd_18blocks"])
+                                  "bf16_bwd_E200", "bf16_E256_C1", "bf16_bwd_9blocks", "bf16_bwd_18blocks"])
 def test_fused_forward_gives_identical_bits(orc, name):
     """Dispatch folded into GEMM1's operand load and combine into GEMM2's epilogue: out (and hact, z_save, y
     where kept) must equal the three-call path bit for bit; the forward-only form writes no dispatch buffer."""
