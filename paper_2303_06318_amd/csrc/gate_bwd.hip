@@ -210,7 +210,15 @@ __global__ void gate_dwg_reduce_t_kernel(const float *partial, float *d_w_gate, 
     if (i >= (int64_t)E * h) return;
     const int j = (int)(i / h), k = (int)(i - (int64_t)j * h);
     float s = 0.f;
-    for (int c = 0; c < nchunks; ++c) s += partial[((int64_t)c * Epad + j) * h + k];
+    int c = 0;
+    for (; c + 8 <= nchunks; c += 8) {            // 8 loads in flight, summed in chunk order
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = partial[((int64_t)(c + u) * Epad + j) * h + k];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; c < nchunks; ++c) s += partial[((int64_t)c * Epad + j) * h + k];
     d_w_gate[(int64_t)k * E + j] = s;
 }
 
