@@ -94,8 +94,8 @@ const char *moe_last_error(void);   /* thread-local text of the last failure in 
 int moe_version(void);
 
 /*
- * Gate + routing (Section 3, step 3: "each GPU applies the MoE routing function to its local
- * tokens"; Section 1: the function is parameterised and maps each token to exactly one expert).
+ * Gate + routing (Section 3, step 3: the routing function runs on every GPU over the tokens that
+ * GPU holds; Section 1: the function is parameterised and maps each token to exactly one expert).
  *   logits[t,j] = sum_k x[t,k] w_gate[k,j]  (+ logit_bias[j])      fp32
  *   e_t   = lowest j attaining max_j logits[t,j]
  *   probs = softmax_j(logits[t,:]),  p_t = probs[t,e_t]
