@@ -122,7 +122,11 @@ moe_status_t moe_gate(const moe_shape_t *shape, const void *x, const float *w_ga
  * Empty slots (s >= kept[e]) are NOT written: the padding of an expert's chunk carries no
  * information, nothing in this library reads it (every later step takes kept[e] rows), and
  * filling it would add up to (capacity_factor - 1) / capacity_factor of the step's HBM writes.
- * A caller that ships whole chunks to another GPU clears buf once when it allocates it.
+ * After a call, rows kept[e] .. C-1 of expert e hold whatever they held before (an earlier step's
+ * tokens when kept[e] has shrunk, not zeros).  A caller that ships whole C-row chunks to another
+ * GPU therefore either sends kept[e] along with chunk e, or clears rows kept[e] .. C-1 itself in
+ * every step; clearing buf once at allocation is not enough.  The same holds for the unwritten rows
+ * of y, d_y and d_buf.
  *   x [T,h], token_of_slot [E,C], buf [E,C,h].
  */
 moe_status_t moe_dispatch(const moe_shape_t *shape, const void *x, const int32_t *token_of_slot, void *buf,

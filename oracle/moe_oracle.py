@@ -24,6 +24,9 @@ _LIB = os.path.join(_HERE, "libmoe_oracle.so")
 ACT_GELU_ERF, ACT_GELU_TANH = 0, 1
 
 
+_LIB_SAN = os.path.join(_HERE, "libmoe_oracle_san.so")
+
+
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (plain -O2, OpenMP for the outer loops)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
@@ -32,14 +35,34 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized(force: bool = False) -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (host code only); any report
+    aborts the process.  Loaded instead of the plain library when MOE_ORACLE_SANITIZE=1 is set, in a
+    process that was started with the sanitizer runtime preloaded (tests/test_oracle_sanitizers.py)."""
+    if force or not os.path.exists(_LIB_SAN) or os.path.getmtime(_LIB_SAN) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+               "-fno-sanitize-recover=all", "-fopenmp", "-fPIC", "-shared", "-std=gnu11", "-o", _LIB_SAN, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB_SAN
+
+
+def sanitizer_runtime() -> str:
+    """Path of gcc's AddressSanitizer runtime (what such a process preloads)."""
+    return subprocess.run(["gcc", "-print-file-name=libasan.so"], check=True, capture_output=True,
+                          text=True).stdout.strip()
+
+
 _lib = None
 
 
 def lib():
     global _lib
     if _lib is None:
-        build()
-        L = C.CDLL(_LIB)
+        if os.environ.get("MOE_ORACLE_SANITIZE") == "1":
+            L = C.CDLL(build_sanitized())
+        else:
+            build()
+            L = C.CDLL(_LIB)
         i64, i32, p, dbl = C.c_int64, C.c_int32, C.c_void_p, C.c_double
         L.orc_act.restype = dbl
         L.orc_act.argtypes = [dbl, i32]

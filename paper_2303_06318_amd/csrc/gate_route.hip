@@ -248,22 +248,6 @@ size_t gate_ws_bytes(const moe_shape_t *sh) {
     return ((planes + 255) / 256) * 256 + ((hist + 255) / 256) * 256;
 }
 
-// tokens per workgroup / 16, waves per workgroup and k-steps in flight per wave, by number of 16-expert tiles
-#ifndef GATE_R1
-#define GATE_R1 4
-#define GATE_NW1 8
-#define GATE_U1 4
-#endif
-#ifndef GATE_R2
-#define GATE_R2 4
-#define GATE_NW2 8
-#define GATE_U2 2
-#endif
-#ifndef GATE_R4
-#define GATE_R4 4
-#define GATE_NW4 8
-#define GATE_U4 2
-#endif
 template <int NT, int R, int NW, int U>
 static void launch_gate_bf16(const moe_shape_t *sh, const void *x, const bf16_t *planes, const float *bias,
                              float *logits, float *probs, int32_t *expert, float *gate_p, hipStream_t s) {
@@ -294,10 +278,11 @@ moe_status_t run_gate(const moe_shape_t *sh, const void *x, const float *w_gate,
         const int64_t n = (int64_t)NT * 16 * sh->h;
         hipLaunchKernelGGL(gate_split_wg_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, w_gate, planes,
                            sh->h, sh->E, NT * 16);
+        // template arguments: 16-expert tiles, tokens per workgroup / 16, waves, k-steps in flight per wave
         switch (NT) {
-            case 1: launch_gate_bf16<1, GATE_R1, GATE_NW1, GATE_U1>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
-            case 2: launch_gate_bf16<2, GATE_R2, GATE_NW2, GATE_U2>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
-            case 4: launch_gate_bf16<4, GATE_R4, GATE_NW4, GATE_U4>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
+            case 1: launch_gate_bf16<1, 4, 8, 4>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
+            case 2: launch_gate_bf16<2, 4, 8, 2>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
+            case 4: launch_gate_bf16<4, 4, 8, 2>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
             case 8: launch_gate_bf16<8, 1, 4, 4>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
             default: launch_gate_bf16<16, 1, 4, 4>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
         }

@@ -23,39 +23,18 @@
 #include <type_traits>
 #include "moe_common.h"
 
-// Timing experiments only; every non-zero variant computes wrong results and is never built into
-// the library.  1: no global->LDS loads; 5: no LDS fragment reads; 6: neither (MFMA and barriers
-// only); 7: every k-tile re-reads k-tile 0 (loads hit the vector L1); 8: k wraps after 8 tiles
-// (loads hit L2).  MOE_GEMM_TL: each workgroup writes {wall start, wall end, shader cycles, tile id}
-// to d.C2 (4 x int64 per workgroup) for a timeline of the launch.
-#ifndef MOE_GEMM_DBG
-#define MOE_GEMM_DBG 0
-#endif
-
 namespace moe {
 
-constexpr int DBG = MOE_GEMM_DBG;
-#ifndef MOE_GEMM_TL
-#define MOE_GEMM_TL 0
-#endif
-constexpr bool TL = MOE_GEMM_TL != 0;
-#ifndef MOE_GEMM_BK
-#define MOE_GEMM_BK 32
-#endif
-constexpr int BM = 256, BN = 256, BK = MOE_GEMM_BK, GEMM_THREADS = 512;
-static_assert(BK == 32 || BK == 64, "k-tile depth");
+constexpr int BM = 256, BN = 256, BK = 32, GEMM_THREADS = 512;
 constexpr int KS = BK / 16;                    // MFMA k-steps per k-tile
 constexpr int CPW = BK / 16;                   // 1 KB chunks per wave, operand and k-tile
 constexpr int KC_ROW = BK * 2;                 // bytes of one KC row in LDS
 constexpr int KC_G = BK / 8;                   // 16-byte granules per KC row
-constexpr int KC_SWZ_SHIFT = BK == 32 ? 2 : 1; // rows per 256 bytes = 4 (BK 32) or 2 (BK 64)
+constexpr int KC_SWZ_SHIFT = 2;                // rows per 256 bytes
 constexpr int LIGHT_BLOCKS = 4;                // an expert with at most this many 32-row blocks is one "light" tile
 constexpr int MAXB = 9;                        // 32-row blocks of a tile when A is a KC operand: 8, or 9 in a "tall" tile
 constexpr int A_ROWS = MAXB * 32;              // rows of the A stage and of the epilogue staging tile
-#ifndef MOE_GEMM_NSTAGE
-#define MOE_GEMM_NSTAGE (MOE_GEMM_BK == 32 ? 4 : 2)
-#endif
-constexpr int NSTAGE = MOE_GEMM_NSTAGE;                      // LDS stages; tiles are requested NSTAGE-1 k-tiles ahead
+constexpr int NSTAGE = 4;                      // LDS stages; tiles are requested NSTAGE-1 k-tiles ahead
 constexpr int OPER_BYTES = 256 * BK * 2;       // 256 rows or columns of one operand's k-tile (16 KB)
 constexpr int OPER_A_BYTES = A_ROWS * BK * 2;  // A's part of a stage: room for the ninth block of a tall tile (18 KB)
 constexpr int STAGE_BYTES = OPER_A_BYTES + OPER_BYTES;
@@ -423,8 +402,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
     int tid = tid0;
     asm volatile("" : "+v"(tid));
     const int lane = tid & 63;
-    const long long t_entry = TL ? clock64() : 0;
-    const long long w_entry = TL ? wall_clock64() : 0;
     const int tile_idx = __builtin_amdgcn_readfirstlane(s_next[4]);
     if (tile_idx < 0) break;
     const int ent0 = __builtin_amdgcn_readfirstlane(s_next[0]);
@@ -433,7 +410,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
     const int nti = __builtin_amdgcn_readfirstlane(s_next[1]);
     const int blk0 = __builtin_amdgcn_readfirstlane(s_next[2]);
     const int kept = __builtin_amdgcn_readfirstlane(s_next[3]);
-    const long long t_sched = TL ? clock64() : 0;
     const bool tall = !AXC && nblk == MAXB;
 
     const int Me = d.rows_from_kept ? kept : d.M;
@@ -505,9 +481,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
     // Fragment reads and MFMAs of one k-step, in halves: half 0 covers a[0], a[1], b[0], b[1] and
     // block rows 0-1, half 1 a[2], a[3] and block rows 2-3.  In a partial m-tile (full = false)
     // blocks without valid rows are skipped.
-    bool rd_enable = true;
     auto rd_half = [&](bf16x8(&af)[4], bf16x8(&bf)[2], int stage, int ks, int half, auto full) {
-        if ((DBG == 5 || DBG == 6) && !rd_enable) return;
         const char *ta = smem + stage * STAGE_BYTES, *tb = ta + OPER_A_BYTES;
         if (half == 0 && (decltype(full)::value || nvi > 0)) {
 #pragma unroll
@@ -528,7 +502,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
     };
     // one of the 2*CPW one-KB chunk loads this wave contributes to a k-tile (CPW per operand)
     auto request_piece = [&](int kt, int stage, int piece) {
-        const int k0 = (DBG == 7 ? 0 : DBG == 8 ? (kt & 7) : kt) * BK;
+        const int k0 = kt * BK;
         const uint32_t base = smem_addr + stage * STAGE_BYTES;
         if (piece < CPW) {
             const uint32_t kadd = AXC ? (uint32_t)k0 * d.lda * 2u : (uint32_t)k0 * 2u;
@@ -543,12 +517,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
     };
     auto request_extra = [&](int kt, int stage) {     // tall tiles, waves 0 and 5 only
         static_assert(BK == 32, "16 rows of 64 bytes per chunk");
-        const int k0 = (DBG == 7 ? 0 : DBG == 8 ? (kt & 7) : kt) * BK;
+        const int k0 = kt * BK;
         const uint32_t voff = k0 < kthrx ? offx + (uint32_t)k0 * 2u : OOB;
         load_to_lds(A, smem_addr + stage * STAGE_BYTES + (uint32_t)(256 + 16 * xw) * KC_ROW, voff);
     };
     auto rd_extra = [&](int stage) {
-        if ((DBG == 5 || DBG == 6) && !rd_enable) return;
         const char *ta = smem + stage * STAGE_BYTES, *tb = ta + OPER_A_BYTES;
         ax0 = fa.read(ta, 8 - (wm >> 5), 0);
         ax1 = fa.read(ta, 8 - (wm >> 5), 1);
@@ -563,7 +536,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
         mma_half(af, bf, 1, full);
     };
     auto request = [&](int kt, int stage) {
-        if (DBG == 1 || DBG == 6) return;
 #pragma unroll
         for (int piece = 0; piece < 2 * CPW; ++piece) request_piece(kt, stage, piece);
     };
@@ -571,20 +543,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
     for (int i = 0; i < 4; ++i) a1[i] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
     for (int j = 0; j < 2; ++j) b1[j] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-    if (DBG != 0) {      // experiments: operands must look like real data (power draw depends on it)
-        for (int i = tid; i < NSTAGE * STAGE_BYTES / 4; i += GEMM_THREADS) {
-            uint32_t r = (uint32_t)i * 2654435761u + (uint32_t)tile_idx;
-            r ^= r >> 15; r *= 2246822519u; r ^= r >> 13;
-            ((uint32_t *)smem)[i] = (r & 0x807f807fu) | 0x3c003c00u | ((r >> 3) & 0x03800380u);
-        }
-        __syncthreads();
-        if (DBG == 5 || DBG == 6) {     // fragments read once, from the random fill
-            rd_half(a0, b0, 0, 0, 0, std::true_type{}); rd_half(a0, b0, 0, 0, 1, std::true_type{});
-            rd_half(a1, b1, 0, 1, 0, std::true_type{}); rd_half(a1, b1, 0, 1, 1, std::true_type{});
-            __syncthreads();
-            rd_enable = false;
-        }
-    }
     // Main loop, "ping-pong" form.  Waves w and w+4 share a SIMD.  Each wave alternates a memory
     // phase M (request tile kt+3, read all fragments of tile kt from LDS) and a compute phase C
     // (16 MFMAs), every phase ending in a workgroup barrier; waves 4-7 run half an iteration behind
@@ -600,7 +558,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
     const bool late_group = wave >= 4;
     auto main_loop = [&](auto full, auto tallc) {
         constexpr bool TALLV = !AXC && decltype(tallc)::value;
-        const bool five = TALLV && DBG != 11 && has_x;   // this wave has 5 loads per k-tile in flight
+        const bool five = TALLV && has_x;   // this wave has 5 loads per k-tile in flight
         // A wave waits until only the loads of the two newest k-tiles are outstanding.  The two waves
         // that load the ninth block issue that fifth load in the MFMA phase (the memory phase is the
         // longer one), so at the end of a memory phase it has not been issued yet for the newest tile.
@@ -631,7 +589,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
             rd_half(a0, b0, stage, 0, 1, full);
             rd_half(a1, b1, stage, 1, 0, full);
             rd_half(a1, b1, stage, 1, 1, full);
-            if (TALLV && DBG != 12) rd_extra(stage);
+            if (TALLV) rd_extra(stage);
             __builtin_amdgcn_sched_barrier(0);
             wait_end_of_M();
             __builtin_amdgcn_s_barrier();
@@ -640,9 +598,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
             __builtin_amdgcn_s_setprio(1);
             mma(a0, b0, full);
             if (five) request_extra(kt + NSTAGE - 1, prev);
-            if (TALLV && DBG != 13) mma_extra(bx0, ax0);
+            if (TALLV) mma_extra(bx0, ax0);
             mma(a1, b1, full);
-            if (TALLV && DBG != 13) mma_extra(bx1, ax1);
+            if (TALLV) mma_extra(bx1, ax1);
             __builtin_amdgcn_s_setprio(0);
             __builtin_amdgcn_sched_barrier(0);
             wait_end_of_C();
@@ -826,11 +784,6 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
             put4(pos, g);
         });
         flush(C);
-    }
-    if (TL && tid == 0 && d.C2) {
-        long long *o = (long long *)d.C2 + (int64_t)tile_idx * 4;
-        o[0] = w_entry; o[1] = wall_clock64(); o[2] = clock64() - t_entry;
-        o[3] = nblk | (e << 8) | (myx << 20) | ((light ? 1 : 0) << 24) | ((long long)(t_sched - t_entry) << 32);
     }
     // the staging tile is reused by the next tile; s_next was last read before the main loop
     if (tid == 0) {

@@ -478,16 +478,20 @@ moe_status_t moe_expert_ffn_bwd(const moe_shape_t *shape, const void *d_y, const
     };
     if ((st = hip_ok(hipEventRecord(ss->fork, hs), "event record")) != MOE_OK) return st;
     if ((st = hip_ok(hipStreamWaitEvent(ss->stream, ss->fork, 0), "stream wait")) != MOE_OK) return st;
-    if ((st = launch_gemm_bf16(g[0], hs)) != MOE_OK) return st;
-    moe_status_t side = launch_gemm_bf16(g[1], ss->stream);
-    if (side == MOE_OK) side = hip_ok(hipEventRecord(ss->mid, hs), "event record");
-    if (side == MOE_OK) side = hip_ok(hipStreamWaitEvent(ss->stream, ss->mid, 0), "stream wait");
-    if (side == MOE_OK) side = launch_gemm_bf16(g[2], ss->stream);
-    // whatever happened on the side stream, the caller's stream waits for what was enqueued there
-    st = launch_gemm_bf16(g[3], hs);
+    // From here on the side stream is tied to the caller's stream (under stream capture it has joined the
+    // capture), so whatever fails below, the join at the end is still enqueued before the call returns.
+    moe_status_t main_st = launch_gemm_bf16(g[0], hs);
+    moe_status_t side = MOE_OK;
+    if (main_st == MOE_OK) {
+        side = launch_gemm_bf16(g[1], ss->stream);
+        if (side == MOE_OK) side = hip_ok(hipEventRecord(ss->mid, hs), "event record");
+        if (side == MOE_OK) side = hip_ok(hipStreamWaitEvent(ss->stream, ss->mid, 0), "stream wait");
+        if (side == MOE_OK) side = launch_gemm_bf16(g[2], ss->stream);
+        main_st = launch_gemm_bf16(g[3], hs);
+    }
     moe_status_t j = hip_ok(hipEventRecord(ss->join, ss->stream), "event record");
     if (j == MOE_OK) j = hip_ok(hipStreamWaitEvent(hs, ss->join, 0), "stream wait");
-    return side != MOE_OK ? side : (st != MOE_OK ? st : j);
+    return main_st != MOE_OK ? main_st : (side != MOE_OK ? side : j);
 }
 
 moe_status_t moe_dispatch_bwd(const moe_shape_t *shape, const void *d_buf, const int32_t *expert, const int32_t *slot,

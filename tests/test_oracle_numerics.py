@@ -43,6 +43,29 @@ def test_gelu_limits(orc):
             assert abs(fd - orc.act_grad(x, mode)) < 1e-8
 
 
+def test_gelu_derivative_array_against_autograd_and_differences(orc):
+    """The array form of act' (the checker of the z_save the GPU keeps for the backward): against the
+    library's GeLU differentiated by autograd in fp64, against central differences of the oracle's own
+    forward, and against the closed form with math.erf -- over a ragged 3-d array, so that a wrong
+    length, stride or mode argument shows."""
+    rng = np.random.default_rng(11)
+    z = np.concatenate([rng.standard_normal(997) * 2.5, [-9.0, -1e-3, 0.0, 1e-3, 9.0, 30.0, -30.0]]).reshape(4, 251)
+    for mode, approx in ((orc.ACT_GELU_ERF, "none"), (orc.ACT_GELU_TANH, "tanh")):
+        g = orc.act_grad_array(z, mode)
+        assert g.shape == z.shape and g.dtype == np.float64
+        zt = torch.from_numpy(z.copy()).requires_grad_(True)
+        (ref,) = torch.autograd.grad(torch.nn.functional.gelu(zt, approximate=approx).sum(), zt)
+        assert np.abs(g - ref.numpy()).max() < 1e-13
+        fd = np.array([(orc.act(v + 1e-6, mode) - orc.act(v - 1e-6, mode)) / 2e-6 for v in z.ravel()]).reshape(z.shape)
+        assert np.abs(g - fd).max() < 1e-8
+    closed = np.array([0.5 * (1.0 + math.erf(v / math.sqrt(2.0))) + v * math.exp(-0.5 * v * v) / math.sqrt(2.0 * math.pi)
+                       for v in z.ravel()]).reshape(z.shape)
+    assert np.abs(orc.act_grad_array(z, orc.ACT_GELU_ERF) - closed).max() < 1e-15
+    # the two forms differ (by up to a few 1e-4 near |z| = 2): a swapped mode argument cannot pass both
+    assert np.abs(orc.act_grad_array(z, 0) - orc.act_grad_array(z, 1)).max() > 1e-4
+    assert orc.act_grad_array(np.zeros((0,)), 0).shape == (0,)
+
+
 # ---------------------------------------------------------------- softmax / logits
 def test_softmax_against_library_and_invariants(orc):
     rng = np.random.default_rng(0)
