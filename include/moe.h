@@ -152,6 +152,29 @@ moe_status_t moe_expert_ffn_fwd(const moe_shape_t *shape, const void *buf, const
                                 size_t ws_bytes, void *stream);
 
 /*
+ * moe_expert_ffn_fwd for callers that cannot allocate or size a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation, same kernels and
+ * bit-identical results; the only scratch of the call, the tile plans of its two GEMMs (fetch counters
+ * and tile queues), lives in an array inside the library's device image instead of a caller workspace.
+ * The call allocates and frees nothing (no hipMalloc, no hipFree, no allocating library routine).
+ *  - hact must be given (without a workspace there is nowhere else to keep GeLU(z)); z_save may be NULL.
+ *  - Limit: the two plans must fit MOE_STATIC_SCRATCH_BYTES; a plan takes
+ *    128 + 16 * E * ceil(C / 256) * ceil(N / 256) bytes (N = f for the first GEMM, h for the second),
+ *    rounded up to 256.  Larger shapes return MOE_ERR_UNSUPPORTED (nothing is launched) and must use
+ *    moe_expert_ffn_fwd.
+ *    The 6.7B-base shard (E=16, C=1280, h=f=4096) needs 41 KB.
+ *  - Each GPU holds one such array for the life of the process and every call on that GPU uses it:
+ *    two calls that overlap on one GPU (different streams, or different host threads) race on the
+ *    plans and give undefined results; calls ordered on one stream are fine.  The array keeps the
+ *    previous call's contents; the call rewrites every word it reads before the GEMMs start.
+ *  - The array's device address is looked up on the first call on each device (not an allocation);
+ *    make that first call outside stream capture.
+ */
+#define MOE_STATIC_SCRATCH_BYTES (256u * 1024u)
+moe_status_t moe_expert_ffn_fwd_static(const moe_shape_t *shape, const void *buf, const void *w1, const void *w2,
+                                       const int32_t *kept, void *z_save, void *hact, void *y, void *stream);
+
+/*
  * Combine (Section 3, step 7, local half: tokens come back to their original position; the
  * gate probability weights the expert's output).
  *   out[t,:] = gate_p[t] * y[expert[t], slot[t], :]  if slot[t] >= 0, else 0.

@@ -218,6 +218,39 @@ static SideStream *side_stream() {
     return ss.ok ? &ss : nullptr;
 }
 
+// Scratch of the entry point that allocates nothing (moe_expert_ffn_fwd_static): the tile plans of its two
+// GEMMs (fetch counters, share boundaries, tile queue) live in this array instead of a caller workspace.
+// Every GPU the library runs on holds its own copy at its own address until the process ends; in host
+// code the array's name is only a handle for hipGetSymbolAddress, never a device address.
+constexpr size_t STATIC_SCRATCH_BYTES = MOE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+// Device address of this GPU's copy of `scratch`, resolved once per device with that device current.
+static moe_status_t static_scratch(void **out) {
+    static void *per_device[64] = {};
+    static std::mutex mu;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= 64) {
+        set_error("moe_expert_ffn_fwd_static: no current device (%s)", hipGetErrorString(e));
+        return MOE_ERR_HIP;
+    }
+    std::lock_guard<std::mutex> lock(mu);
+    if (per_device[dev] == nullptr) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || ptr == nullptr) {
+            set_error("moe_expert_ffn_fwd_static: hipGetSymbolAddress(scratch) failed on device %d: %s", dev,
+                      hipGetErrorString(e));
+            (void)hipGetLastError();
+            return MOE_ERR_HIP;
+        }
+        per_device[dev] = ptr;
+    }
+    *out = per_device[dev];
+    return MOE_OK;
+}
+
 static moe_status_t check_ws(const char *fn, const void *ws, size_t have, size_t need) {
     if (need == 0) return MOE_OK;
     if (ws == nullptr || misaligned(ws)) {
@@ -228,6 +261,26 @@ static moe_status_t check_ws(const char *fn, const void *ws, size_t have, size_t
         set_error("%s: workspace too small: %zu bytes given, %zu needed", fn, have, need);
         return MOE_ERR_WORKSPACE_TOO_SMALL;
     }
+    return MOE_OK;
+}
+
+// The two forward GEMMs (arguments already validated; hact is a real array; `plans` holds
+// ffn_plan_bytes(G_FWD1..G_FWD2) bytes on the bf16 path and is unused on the fp32 path).
+static moe_status_t ffn_fwd_launch(const moe_shape_t &s, const void *buf, const void *w1, const void *w2,
+                                   const int32_t *kept, void *z_save, void *hact, void *y, char *plans,
+                                   hipStream_t hs) {
+    const bool bf = s.dtype == MOE_BF16;
+    moe_status_t st;
+    GemmDesc g[2] = {ffn_gemm(s, G_FWD1), ffn_gemm(s, G_FWD2)};
+    g[0].A = buf; g[0].B = w1; g[0].C = hact; g[0].C2 = z_save; g[0].kept = kept;
+    g[1].A = hact; g[1].B = w2; g[1].C = y; g[1].kept = kept;
+    if (bf) {
+        char *pl = plans;
+        for (int i = 0; i < 2; ++i) { g[i].plan = pl; pl += gemm_bf16_plan_bytes(g[i]); }
+        if ((st = launch_gemm_bf16_plans(g, 2, hs)) != MOE_OK) return st;
+    }
+    for (int i = 0; i < 2; ++i)
+        if ((st = bf ? launch_gemm_bf16(g[i], hs) : launch_gemm_f32(g[i], hs)) != MOE_OK) return st;
     return MOE_OK;
 }
 
@@ -311,21 +364,34 @@ moe_status_t moe_expert_ffn_fwd(const moe_shape_t *shape, const void *buf, const
     const bool own_hact = hact == nullptr;
     st = check_ws("moe_expert_ffn_fwd", ws, ws_bytes, ffn_fwd_ws_bytes(shape, own_hact));
     if (st != MOE_OK) return st;
-    const moe_shape_t &s = *shape;
-    const bool bf = s.dtype == MOE_BF16;
-    hipStream_t hs = (hipStream_t)stream;
     if (own_hact) hact = ws;                   // not kept for the backward: it will be recomputed there
-    GemmDesc g[2] = {ffn_gemm(s, G_FWD1), ffn_gemm(s, G_FWD2)};
-    g[0].A = buf; g[0].B = w1; g[0].C = hact; g[0].C2 = z_save; g[0].kept = kept;
-    g[1].A = hact; g[1].B = w2; g[1].C = y; g[1].kept = kept;
-    if (bf) {
-        char *pl = (char *)ws + (own_hact ? dz_bytes(shape) : 0);
-        for (int i = 0; i < 2; ++i) { g[i].plan = pl; pl += gemm_bf16_plan_bytes(g[i]); }
-        if ((st = launch_gemm_bf16_plans(g, 2, hs)) != MOE_OK) return st;
+    return ffn_fwd_launch(*shape, buf, w1, w2, kept, z_save, hact, y,
+                          (char *)ws + (own_hact ? dz_bytes(shape) : 0), (hipStream_t)stream);
+}
+
+moe_status_t moe_expert_ffn_fwd_static(const moe_shape_t *shape, const void *buf, const void *w1, const void *w2,
+                                       const int32_t *kept, void *z_save, void *hact, void *y, void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    REQUIRE_PTR(buf);
+    REQUIRE_PTR(w1);
+    REQUIRE_PTR(w2);
+    REQUIRE_PTR(kept);
+    OPTIONAL_PTR(z_save);
+    REQUIRE_PTR(hact);
+    REQUIRE_PTR(y);
+    const size_t need = ffn_plan_bytes(shape, G_FWD1, G_FWD2);
+    if (need > STATIC_SCRATCH_BYTES) {
+        set_error("moe_expert_ffn_fwd_static: the tile plans of this shape need %zu bytes, the library's static scratch "
+                  "holds %zu (E=%d C=%lld h=%d f=%d); use moe_expert_ffn_fwd with a workspace",
+                  need, STATIC_SCRATCH_BYTES, shape->E, (long long)shape->C, shape->h, shape->f);
+        return MOE_ERR_UNSUPPORTED;
     }
-    for (int i = 0; i < 2; ++i)
-        if ((st = bf ? launch_gemm_bf16(g[i], hs) : launch_gemm_f32(g[i], hs)) != MOE_OK) return st;
-    return MOE_OK;
+    void *plans = nullptr;
+    if (need > 0 && (st = static_scratch(&plans)) != MOE_OK) return st;
+    // the plan kernel zeroes the fetch counters and rewrites every word the GEMMs read, so what the previous
+    // call left in the array does not matter
+    return ffn_fwd_launch(*shape, buf, w1, w2, kept, z_save, hact, y, (char *)plans, (hipStream_t)stream);
 }
 
 moe_status_t moe_expert_ffn_fwd_fused(const moe_shape_t *shape, const void *x, const void *buf,

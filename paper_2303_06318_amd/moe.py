@@ -19,7 +19,9 @@ MOE_GELU_ERF, MOE_GELU_TANH = 0, 1
 
 EXPORTS = ["moe_capacity", "moe_workspace_bytes", "moe_status_string", "moe_last_error", "moe_version", "moe_gate",
            "moe_dispatch", "moe_expert_ffn_fwd", "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd",
-           "moe_dispatch_bwd", "moe_gate_bwd", "moe_adamw_tiled", "moe_expert_ffn_fwd_fused"]
+           "moe_dispatch_bwd", "moe_gate_bwd", "moe_adamw_tiled", "moe_expert_ffn_fwd_fused",
+           "moe_expert_ffn_fwd_static"]
+MOE_STATIC_SCRATCH_BYTES = 256 * 1024
 
 
 class Shape(C.Structure):
@@ -62,6 +64,7 @@ def lib():
             "moe_gate": [sp] + [vp] * 11 + [vp, sz, vp],
             "moe_dispatch": [sp, vp, vp, vp, vp],
             "moe_expert_ffn_fwd": [sp] + [vp] * 7 + [vp, sz, vp],
+            "moe_expert_ffn_fwd_static": [sp] + [vp] * 7 + [vp],
             "moe_combine": [sp] + [vp] * 5 + [vp],
             "moe_expert_ffn_fwd_fused": [sp] + [vp] * 12 + [vp, sz, vp],
             "moe_combine_bwd": [sp] + [vp] * 7 + [vp],
@@ -137,6 +140,11 @@ def moe_dispatch(shape, x, token_of_slot, buf, stream=None):
 def moe_expert_ffn_fwd(shape, buf, w1, w2, kept, z_save, hact, y, ws, stream=None):
     _check(lib().moe_expert_ffn_fwd(C.byref(shape), _ptr(buf), _ptr(w1), _ptr(w2), _ptr(kept), _ptr(z_save),
                                     _ptr(hact), _ptr(y), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def moe_expert_ffn_fwd_static(shape, buf, w1, w2, kept, z_save, hact, y, stream=None):
+    _check(lib().moe_expert_ffn_fwd_static(C.byref(shape), _ptr(buf), _ptr(w1), _ptr(w2), _ptr(kept), _ptr(z_save),
+                                           _ptr(hact), _ptr(y), _stream(stream)))
 
 
 def moe_expert_ffn_fwd_fused(shape, x, buf, token_of_slot, slot, gate_p, w1, w2, kept, z_save, hact, y, out, ws,

@@ -147,6 +147,19 @@ def test_fused_forward_arguments():
     assert L.moe_expert_ffn_fwd_fused(C.byref(sh), p, None, p, p, p, p, p, p, None, None, None, p, p, 64, None) == moe.MOE_ERR_WORKSPACE_TOO_SMALL
 
 
+def test_static_scratch_forward_arguments():
+    """The entry point without a workspace refuses, before anything touches the GPU, a missing hact and a
+    shape whose tile plans exceed the library's static array."""
+    L = moe.lib()
+    p = C.c_void_p(4096)
+    ok = moe.make_shape(16384, 4096, 16, 4096, 1280)
+    assert L.moe_expert_ffn_fwd_static(C.byref(ok), p, p, p, p, None, None, p, None) == moe.MOE_ERR_INVALID_ARG
+    assert b"hact" in L.moe_last_error()
+    big = moe.make_shape(1 << 18, 2048, 256, 2048, 1024)     # 2 x (128 + 16 * 256 * 4 * 8) bytes of plans > 256 KiB
+    assert L.moe_expert_ffn_fwd_static(C.byref(big), p, p, p, p, None, p, p, None) == moe.MOE_ERR_UNSUPPORTED
+    assert b"static scratch" in L.moe_last_error() and str(moe.MOE_STATIC_SCRATCH_BYTES).encode() in L.moe_last_error()
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(moe, "_lib", None)
     monkeypatch.setattr(moe, "LIB_PATH", "/nonexistent/libmoe_ted.so")
