@@ -26,10 +26,26 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per GEMM launch (average over the launches of a step) from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs, scaled by what the same counters read for a plain 1 GiB copy
-# (profiles/gemm_bf16_cfg5_fwdbwd.md, section 2); keyed by workload name, None where not measured.
-MEASURED_GEMM_TRAFFIC_BYTES = {"cfg5_6p7b_tp4_fwdbwd": 1.209e9}
+RIDGE_ROWS = 300     # kept rows per expert below which an expert GEMM is bound by streaming its weights (peak flops / peak bytes)
+
+
+def measured_gemm_traffic(workload: str):
+    """HBM bytes per GEMM launch (average over the launches of a step) as measured with rocprofv3 --pmc
+    FETCH_SIZE / WRITE_SIZE, scaled by what the same counters read for a plain copy of known size.  Read
+    from the committed summary profiles/gemm_traffic.txt (written by paper_2303_06318_amd/profile_summary.py
+    from the raw counter CSVs of one run; it names the commit it was measured at).  None if the workload
+    has no entry."""
+    path = os.path.join(ROOT, "profiles", "gemm_traffic.txt")
+    if not os.path.exists(path):
+        return None, None
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        kv = dict(item.split("=", 1) for item in line.split())
+        if kv.get("workload") == workload:
+            return float(kv["bytes_per_launch"]), kv.get("commit")
+    return None, None
 
 
 def bench_optimizer(args, wl, layer, w1, w2):
@@ -208,6 +224,30 @@ def main() -> int:
             phase_ms[p] += events[k][i].elapsed_time(events[k][i + 1])
     phase_ms = {p: v / args.steps for p, v in phase_ms.items()}
 
+    step_ms = sorted(events[k][0].elapsed_time(events[k][nev - 1]) for k in range(args.steps))
+    median_ms = step_ms[len(step_ms) // 2] if len(step_ms) % 2 else 0.5 * (step_ms[len(step_ms) // 2 - 1] + step_ms[len(step_ms) // 2])
+    phase_med = {}
+    for i, p in enumerate(phases):
+        v = sorted(events[k][i].elapsed_time(events[k][i + 1]) for k in range(args.steps))
+        phase_med[p] = v[len(v) // 2]
+
+    # routing alone (softmax + top-1 from stored logits, histogram, slot assignment: three dependent small
+    # launches) against the same number of empty launches: both are latency, not bandwidth
+    def timed_us(fn, reps=50):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+    route_launches = 3
+    route_us = timed_us(lambda: moe.moe_gate(sh, None, None, None, layer.logits, layer.probs, layer.expert, layer.gate_p,
+                                             layer.slot, layer.counts, layer.kept, layer.token_of_slot, layer.ws))
+    floor_us = timed_us(lambda: moe.moe_launch_floor(route_launches))
+
     kept = layer.kept.cpu().numpy().astype(np.int64)
     counts = layer.counts.cpu().numpy().astype(np.int64)
     n_kept = int(kept.sum())
@@ -218,13 +258,30 @@ def main() -> int:
     flops_per_launch = 2.0 * wl.hm * wl.fm * n_kept      # model sizes: zero padding to a multiple of 8 is not work
     avg_launch_ms = gemm_ms / n_launch
     achieved = flops_per_launch / (avg_launch_ms * 1e-3) / 1e12
-    traffic = MEASURED_GEMM_TRAFFIC_BYTES.get(wl.name)
-    roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
-                "kernel": "gemm_bf16_kernel", "launches_per_step": n_launch,
-                "avg_launch_ms": round(avg_launch_ms, 4), "flops_per_launch": flops_per_launch}
-
+    traffic, traffic_commit = measured_gemm_traffic(wl.name)
+    # Which roofline bounds the expert GEMMs: with fewer kept rows per expert than the ridge (peak flops /
+    # peak bytes, about 300 rows) a launch is bound by streaming the weights of the experts that hold rows.
+    n_active = int((kept > 0).sum())
+    rows_per_active = n_kept / max(n_active, 1)
     esz = 2
+    bytes_per_launch = n_active * wl.hm * wl.fm * esz + n_kept * (wl.hm + wl.fm) * esz
+    if rows_per_active < RIDGE_ROWS:
+        gbs = bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(gbs / PEAK_HBM_GBS, 4), "traffic": traffic, "traffic_measured_at_commit": traffic_commit,
+                    "kernel": "gemm_bf16_kernel", "launches_per_step": n_launch,
+                    "avg_launch_ms": round(avg_launch_ms, 4), "bytes_per_launch": bytes_per_launch,
+                    "rows_per_active_expert": round(rows_per_active, 1), "active_experts": n_active,
+                    "mfma_TFLOPs_for_information": round(achieved, 1),
+                    "mfma_frac_for_information": round(achieved / PEAK_BF16_TFLOPS, 4)}
+    else:
+        roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                    "traffic_measured_at_commit": traffic_commit,
+                    "kernel": "gemm_bf16_kernel", "launches_per_step": n_launch,
+                    "avg_launch_ms": round(avg_launch_ms, 4), "flops_per_launch": flops_per_launch,
+                    "bytes_per_launch": bytes_per_launch}
+
     hbm = {
         "gate": (wl.T * wl.hm * esz + wl.hm * wl.E * 4 + wl.T * wl.E * 4 * (2 if wl.backward else 1) + wl.T * 8),
         "dispatch": 2 * n_kept * wl.hm * esz + wl.T * 8,
@@ -264,6 +321,8 @@ def main() -> int:
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_median": round(median_ms, 4),
+        "kept_tokens_per_s": round(n_kept / (ms_per_step * 1e-3), 1),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -278,6 +337,10 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "phase_ms": {p: round(v, 4) for p, v in phase_ms.items()},
+        "phase_ms_median": {p: round(v, 4) for p, v in phase_med.items()},
+        "route": {"us": round(route_us, 2), "launches": route_launches, "empty_launch_floor_us": round(floor_us, 2),
+                  "what": "softmax + top-1 from stored logits, histogram, slot assignment (moe_gate with x = NULL) "
+                          "against the same number of empty kernels, back to back on one stream"},
         "hbm_frac_of_8TBs": hbm_frac,
     }
     if optimizer is not None:

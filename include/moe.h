@@ -94,6 +94,14 @@ const char *moe_last_error(void);   /* thread-local text of the last failure in 
 int moe_version(void);
 
 /*
+ * Measurement aid: enqueues n (0..4096) empty one-wave kernels on `stream`, back to back.  The routing
+ * kernels move a few hundred KB and are bound by launch latency, not by HBM (their cost is quoted in
+ * microseconds); this is the floor those microseconds are read against: the time the GPU needs per
+ * dependent launch when a kernel does nothing.  Nothing is read or written.
+ */
+moe_status_t moe_launch_floor(int32_t n, void *stream);
+
+/*
  * Gate + routing (Section 3, step 3: the routing function runs on every GPU over the tokens that
  * GPU holds; Section 1: the function is parameterised and maps each token to exactly one expert).
  *   logits[t,j] = sum_k x[t,k] w_gate[k,j]  (+ logit_bias[j])      fp32

@@ -284,6 +284,9 @@ static moe_status_t ffn_fwd_launch(const moe_shape_t &s, const void *buf, const 
     return MOE_OK;
 }
 
+// Launch-latency floor: a kernel of one wave that does nothing.
+__global__ void empty_kernel() {}
+
 }  // namespace moe
 
 using namespace moe;
@@ -314,6 +317,15 @@ const char *moe_status_string(moe_status_t s) {
 }
 
 const char *moe_last_error(void) { return g_err; }
+
+moe_status_t moe_launch_floor(int32_t n, void *stream) {
+    if (n < 0 || n > 4096) {
+        set_error("moe_launch_floor: n=%d outside 0..4096", n);
+        return MOE_ERR_INVALID_ARG;
+    }
+    for (int i = 0; i < n; ++i) hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream);
+    return check_launch("moe_launch_floor");
+}
 
 moe_status_t moe_gate(const moe_shape_t *shape, const void *x, const float *w_gate, const float *logit_bias,
                       float *logits, float *probs, int32_t *expert, float *gate_p, int32_t *slot, int32_t *counts,

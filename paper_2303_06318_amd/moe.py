@@ -20,7 +20,7 @@ MOE_GELU_ERF, MOE_GELU_TANH = 0, 1
 EXPORTS = ["moe_capacity", "moe_workspace_bytes", "moe_status_string", "moe_last_error", "moe_version", "moe_gate",
            "moe_dispatch", "moe_expert_ffn_fwd", "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd",
            "moe_dispatch_bwd", "moe_gate_bwd", "moe_adamw_tiled", "moe_expert_ffn_fwd_fused",
-           "moe_expert_ffn_fwd_static"]
+           "moe_expert_ffn_fwd_static", "moe_launch_floor"]
 MOE_STATIC_SCRATCH_BYTES = 256 * 1024
 
 
@@ -65,6 +65,7 @@ def lib():
             "moe_dispatch": [sp, vp, vp, vp, vp],
             "moe_expert_ffn_fwd": [sp] + [vp] * 7 + [vp, sz, vp],
             "moe_expert_ffn_fwd_static": [sp] + [vp] * 7 + [vp],
+            "moe_launch_floor": [i32, vp],
             "moe_combine": [sp] + [vp] * 5 + [vp],
             "moe_expert_ffn_fwd_fused": [sp] + [vp] * 12 + [vp, sz, vp],
             "moe_combine_bwd": [sp] + [vp] * 7 + [vp],
@@ -124,6 +125,10 @@ def moe_workspace_bytes(shape: Shape, for_backward) -> int:
 
 def moe_version() -> int:
     return int(lib().moe_version())
+
+
+def moe_launch_floor(n, stream=None):
+    _check(lib().moe_launch_floor(int(n), _stream(stream)))
 
 
 def moe_gate(shape, x, w_gate, logit_bias, logits, probs, expert, gate_p, slot, counts, kept, token_of_slot, ws,

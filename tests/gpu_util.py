@@ -67,3 +67,69 @@ def kept_rows(a: np.ndarray, kept) -> np.ndarray:
 def tol(wl: synth.Workload) -> float:
     """Relative Frobenius tolerance: 2e-2 for bf16 storage with fp32 accumulation, 1e-5 for fp32."""
     return 2e-2 if wl.dtype == "bf16" else 1e-5
+
+
+# ---------------------------------------------------------------- fine-grained comparisons
+# One norm over a whole tensor hides a wrong tile or row of a large result (a wrong 256 x 256 tile of a
+# 16 x 4096 x 4096 gradient moves the whole-tensor relative error by 0.016).  These helpers apply the
+# tolerance to every row and to every 256 x 256 tile, and bound single elements.
+
+def _sq(a):
+    a = np.asarray(a, np.float64)
+    return a * a
+
+
+def row_errors(g, o):
+    """Relative Frobenius error of every row of a 2-d comparison (rows of norm 0 in the oracle: absolute)."""
+    g = np.asarray(g, np.float64).reshape(-1, g.shape[-1])
+    o = np.asarray(o, np.float64).reshape(-1, o.shape[-1])
+    num = np.sqrt(_sq(g - o).sum(1))
+    den = np.sqrt(_sq(o).sum(1))
+    return num / np.where(den > 0, den, 1.0)
+
+
+def tile_errors(g, o, tile=256):
+    """Relative Frobenius error of every tile x tile block of the last two dimensions (ragged edges kept)."""
+    g = np.asarray(g, np.float64)
+    o = np.asarray(o, np.float64)
+    lead = int(np.prod(g.shape[:-2])) if g.ndim > 2 else 1
+    g = g.reshape(lead, *g.shape[-2:])
+    o = o.reshape(lead, *o.shape[-2:])
+    R, Cn = g.shape[-2:]
+    rb = list(range(0, R, tile)) + [R]
+    cb = list(range(0, Cn, tile))
+    d2 = _sq(g - o)
+    o2 = _sq(o)
+    # column blocks by reduceat along the last axis, then row blocks
+    d2 = np.add.reduceat(np.add.reduceat(d2, cb, axis=2), rb[:-1], axis=1)
+    o2 = np.add.reduceat(np.add.reduceat(o2, cb, axis=2), rb[:-1], axis=1)
+    return np.sqrt(d2) / np.where(o2 > 0, np.sqrt(o2), 1.0)
+
+
+def assert_close_everywhere(name, g, o, t, tile=256, elem_rel=2.0 ** -7, elem_rms=0.03, rows_relative=True):
+    """Every row and every tile x tile block within relative Frobenius t, and every element within
+    elem_rel * |value| + elem_rms * rms(tensor).  The element bound: bf16 storage rounds the result by up
+    to 2^-9 of its value and the bf16 intermediates add an error whose rms was measured at about 3e-3 of
+    the tensor's rms; 2^-7 and 0.03 leave a factor of 4 and of 10 (a ten-sigma outlier) over those."""
+    g = np.asarray(g, np.float64)
+    o = np.asarray(o, np.float64)
+    assert g.shape == o.shape, (name, g.shape, o.shape)
+    assert np.isfinite(g).all(), name + ": non-finite values"
+    if rows_relative:
+        re = row_errors(g, o)
+    else:
+        # rows whose own norm can be far below their rounding error (a row scaled by a dot product whose terms
+        # cancel): every row's error against the root-mean-square row norm instead of its own
+        g2, o2 = g.reshape(-1, g.shape[-1]), o.reshape(-1, o.shape[-1])
+        re = np.sqrt(_sq(g2 - o2).sum(1)) / np.sqrt(_sq(o2).sum(1).mean())
+    assert re.max() <= t, "%s: row %d has relative error %.3e (tolerance %.1e)" % (name, int(re.argmax()), re.max(), t)
+    if g.ndim >= 2 and g.shape[-1] > tile:
+        te = tile_errors(g, o, tile)
+        assert te.max() <= t, "%s: tile %s has relative error %.3e (tolerance %.1e)" % (
+            name, np.unravel_index(int(te.argmax()), te.shape), te.max(), t)
+    rms = float(np.sqrt(_sq(o).mean()))
+    excess = np.abs(g - o) - (elem_rel * np.abs(o) + elem_rms * rms)
+    assert excess.max() <= 0, "%s: element %s off by %.3e beyond the bound (value %.3e, tensor rms %.3e)" % (
+        name, np.unravel_index(int(excess.argmax()), excess.shape), float(np.abs(g - o).reshape(-1)[int(excess.argmax())]),
+        float(o.reshape(-1)[int(excess.argmax())]), rms)
+    return float(re.max())
