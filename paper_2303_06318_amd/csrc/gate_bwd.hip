@@ -338,148 +338,172 @@ __global__ __launch_bounds__(256) void gate_dx_kernel(const float *w_gate, const
     }
 }
 
-// The same sum on the matrix cores, for E <= 64:  d_x[t, c0 .. c0+255] for tiles of 32 tokens.
-// The rank-E product dL Wg^T is one v_mfma_f32_32x32x16_bf16 per 32 x 32 block, 16 experts and term;
-// both factors are split in two bf16 pieces and the three leading products are summed in fp32
-// (error about 2^-16 of the term, far below the bf16 rounding of d_x).  Each of the 4 waves owns 64
-// columns and keeps its Wg^T fragments in registers; the 32 x 256 fp32 result goes through LDS so
-// that the streaming part (gathered row in, sum out) moves 16 contiguous bytes per lane.  A
-// workgroup walks up to 8 token tiles; the token rows and the d_logits rows of the next tile are
-// requested before the arithmetic of the current one.
-template <int KB>       // 16-expert blocks: E <= 16 KB
-__global__ __launch_bounds__(256) void gate_dx_mfma_kernel(const float *w_gate, const float *d_logits, bf16_t *d_x,
-                                                            int64_t T, int h, int E, int tiles_per_wg,
-                                                            const bf16_t *d_buf, const int32_t *expert,
-                                                            const int32_t *slot, int64_t C) {
-    constexpr int TT = 32, GLD = 256 + 4;
-    __shared__ __attribute__((aligned(16))) float G[TT][GLD];
-    __shared__ int32_t srow[256];                   // buffer row of each of the workgroup's tokens, -1 if dropped
+// The same sum for E <= 64 without a transposition through LDS: every wave owns 128 columns and walks
+// its tokens 16 at a time with v_mfma_f32_16x16x32_bf16, result block [16 tokens x 16 column slots].
+// The column a slot stands for is free to choose (it only decides which row of Wg feeds the B operand),
+// so block b (0..7) takes slot n <-> column 8 n + b: after the 8 blocks lane l holds, for each of its 4
+// token rows, the 8 CONSECUTIVE columns 8 (l % 16) .. + 7.  The gathered d_buf row piece (16 bytes) is
+// loaded, the sum is added and the result stored with one 16-byte access per lane, 16 lanes covering 256
+// contiguous bytes of a row; the Wg^T fragments (hi + lo bf16 pieces, 64 registers per 32 experts) stay
+// in registers for the wave's whole token range.  Both factors are split in two bf16 pieces and the three
+// leading products summed in fp32.  LDS only holds the workgroup's small operands (source row of each
+// token, d_logits rows), written once before the loop, so that the loop's only vector-memory traffic is
+// the row stream.
+constexpr int DX_TOKENS = 192;          // tokens per workgroup (4 waves x 128 columns each); a multiple of 48
+template <int KS, bool GATHER>          // 32-expert k-steps (E <= 32 KS); rows gathered from d_buf, or d_x in place
+__global__ __launch_bounds__(256, KS == 1 ? 2 : 1) void gate_dx_rows_kernel(
+    const float *w_gate, const float *d_logits, bf16_t *d_x, int64_t T, int h, int E, const bf16_t *d_buf,
+    const int32_t *expert, const int32_t *slot, int64_t C) {
+    // One dynamic LDS region of 512 rows x (E8 + 4) floats (E8 = E rounded up to 8), used twice: first the
+    // workgroup's 512 rows of Wg, read from memory with coalesced accesses and then picked apart into MFMA
+    // fragments; afterwards the d_logits rows of its tokens.  Behind it, the source row of every token.
+    extern __shared__ __attribute__((aligned(16))) float s_f[];
+    const int E8 = (E + 7) & ~7, LDE = E8 + 4;
+    int32_t *s_row = (int32_t *)(s_f + 512 * LDE);                // DX_TOKENS + 48 entries (-1: no row): requests run ahead
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int c0 = blockIdx.x * 256;
-    // B fragments: lane holds Wg[col][16 kb + 8 (lane / 32) .. + 7], col = c0 + 64 wave + 32 j + lane % 32,
-    // in two bf16 pieces (zeros outside the matrix)
-    bf16x8 bh[2][KB], bl[2][KB];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int col = c0 + wave * 64 + j * 32 + (lane & 31);
-        const float *row = w_gate + (int64_t)(col < h ? col : 0) * E;
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const int k = kb * 16 + 8 * (lane >> 5) + q;
-                const float v = (col < h && k < E) ? row[k] : 0.f;
-                const bf16_t hq = f32_to_bf16(v);
-                bh[j][kb][q] = hq;
-                bl[j][kb][q] = f32_to_bf16(v - bf16_to_f32(hq));
-            }
-    }
-    const int c8 = (tid & 31) * 8;                  // streaming part: 8 columns of one token row
-    const bool cin = c0 + c8 < h;
-    const int64_t t_first = (int64_t)blockIdx.y * tiles_per_wg * TT;
-    // raw d_logits values of the lane's A fragments, loaded one tile ahead
-    float araw[KB][8];
-    auto load_a = [&](int64_t tb) {
-        const int64_t trow = tb + (lane & 31);
-        const float *row = d_logits + (trow < T ? trow : 0) * E;
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const int k = kb * 16 + 8 * (lane >> 5) + q;
-                araw[kb][q] = (trow < T && k < E) ? row[k] : 0.f;
-            }
-    };
-    load_a(t_first);
-    if (d_buf) {                                    // tiles_per_wg * 32 <= 256 tokens: one per thread, all tiles at once
-        int32_t r = -1;
-        if (tid < tiles_per_wg * TT && t_first + tid < T) {
-            const int sl = slot[t_first + tid];
-            if (sl >= 0) r = (int32_t)((int64_t)expert[t_first + tid] * C + sl);
+    const int n16 = lane & 15, g = lane >> 4;
+    const int64_t t_begin = (int64_t)blockIdx.y * DX_TOKENS;
+    const int nt = (int)(T - t_begin < DX_TOKENS ? T - t_begin : DX_TOKENS);     // tokens of this workgroup
+    const int c_first = blockIdx.x * 512;
+    const int ncol = h - c_first < 512 ? h - c_first : 512;       // columns of this workgroup inside the matrix
+    // Loads are unconditional, from clamped (always valid) addresses, and a select zeroes what lies
+    // outside ("&", not "&&": a guarded load becomes a branch around the load plus a full wait).
+    if ((E & 3) == 0) {                                           // 16-byte pieces: rows of Wg are contiguous in memory
+        const int q4 = E >> 2, e4 = E8 >> 2;
+        for (int i = tid; i < 512 * e4; i += 256) {
+            const int c = i / e4, k4 = i - c * e4;
+            const bool in = (c < ncol) & (k4 < q4);
+            const f32x4 v = *(const f32x4 *)(w_gate + (int64_t)(c_first + (c < ncol ? c : 0)) * E + 4 * (k4 < q4 ? k4 : 0));
+            *(f32x4 *)&s_f[c * LDE + 4 * k4] = in ? v : f32x4{0.f, 0.f, 0.f, 0.f};
         }
-        srow[tid] = r;
+    } else {
+        for (int i = tid; i < 512 * E8; i += 256) {
+            const int c = i / E8, k = i - c * E8;
+            const bool in = (c < ncol) & (k < E);
+            const float v = w_gate[(int64_t)(c_first + (c < ncol ? c : 0)) * E + (k < E ? k : 0)];
+            s_f[c * LDE + k] = in ? v : 0.f;
+        }
+    }
+    for (int i = tid; i < DX_TOKENS + 48; i += 256) {
+        const bool tin = i < nt;
+        const int64_t t = t_begin + (tin ? i : 0);
+        int32_t r = (int32_t)t;
+        if (GATHER) {
+            const int sl = slot[t], ex = expert[t];
+            r = sl >= 0 ? ex * (int32_t)C + sl : -1;
+        }
+        s_row[i] = tin ? r : -1;
     }
     __syncthreads();
-    // the 4 token rows of a thread (16 bytes each), requested one tile ahead, in two alternating sets
-    u32x4 raw[4], nxt[4];
-    auto load_rows = [&](int it, u32x4(&dst)[4]) {
-        const int64_t tb = t_first + (int64_t)it * TT;
+    const int cw = c_first + wave * 128;                          // first column of the wave
+    const int col = cw + 8 * n16;                                 // the lane's 8 columns
+    const bool cin = col < h;
+    // The lane's 8 experts of k-step ks start at 32 ks + 8 g; at or beyond E8 they do not exist (zeros).
+    // B fragments: block b, slot n = lane % 16 <-> column col + b.
+    bf16x8 bh[8][KS], bl[8][KS];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int tt = (tid >> 5) + 8 * u;
-            dst[u] = u32x4{0u, 0u, 0u, 0u};
-            if (cin && it < tiles_per_wg && tb + tt < T) {
-                if (d_buf) {
-                    const int r = srow[it * TT + tt];
-                    if (r >= 0) dst[u] = *(const u32x4 *)(d_buf + (int64_t)r * h + c0 + c8);
-                } else {
-                    dst[u] = *(const u32x4 *)(d_x + (tb + tt) * h + c0 + c8);
-                }
-            }
-        }
-    };
-    // One tile: MFMAs into G, then every thread adds its 4 row pieces and writes them.  The row pieces are
-    // waited for only here, at their use, and the next tile's d_logits are requested as soon as this tile's
-    // have been split, so both have most of a tile's time to arrive.
-    auto tile = [&](int it, const u32x4(&rows)[4]) {
-        const int64_t tb = t_first + (int64_t)it * TT;
-        if (it > 0) __syncthreads();                // G of the previous tile has been read
-        bf16x8 ah[KB], al[KB];
+    for (int b = 0; b < 8; ++b) {
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
+        for (int ks = 0; ks < KS; ++ks) {
+            const int k0 = ks * 32 + 8 * g;
+            const bool kin = k0 < E8;
+            const float *p = &s_f[(wave * 128 + 8 * n16 + b) * LDE + (kin ? k0 : 0)];
+            const f32x4 w0 = *(const f32x4 *)p, w1 = *(const f32x4 *)(p + 4);
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                const bf16_t hq = f32_to_bf16(araw[kb][q]);
-                ah[kb][q] = hq;
-                al[kb][q] = f32_to_bf16(araw[kb][q] - bf16_to_f32(hq));
+                const float v = kin ? (q < 4 ? w0[q & 3] : w1[q & 3]) : 0.f;
+                const bf16_t hq = f32_to_bf16(v);
+                bh[b][ks][q] = hq;
+                bl[b][ks][q] = f32_to_bf16(v - bf16_to_f32(hq));
             }
-        if (it + 1 < tiles_per_wg && tb + TT < T) load_a(tb + TT);
-        f32x16 acc[2];
+        }
+    }
+    __syncthreads();                                              // the Wg rows have been read: the region is reused
+    for (int i = tid; i < (DX_TOKENS + 16) * E8; i += 256) {
+        const int tt = i / E8, k = i - tt * E8;
+        const bool in = (tt < nt) & (k < E);
+        const float v = d_logits[(t_begin + (tt < nt ? tt : 0)) * E + (k < E ? k : 0)];
+        s_f[tt * LDE + k] = in ? v : 0.f;
+    }
+    __syncthreads();
+    if (cw >= h) return;                                          // whole wave outside the matrix (no barrier below)
+    // Rows move through buffer resources: an offset beyond the resource's size (the marker below, for a
+    // dropped token, a token past the end, a column past h) makes a load return zeros and a store do nothing,
+    // so the stream has no branches and the compiler's wait counts are exact.
+    constexpr uint32_t OUTSIDE = 0x80000000u;                      // the host checks that both arrays are shorter
+    const int64_t src_rows = GATHER ? (int64_t)E * C : T;
+    const __amdgpu_buffer_rsrc_t src_r = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>(GATHER ? d_buf : d_x), 0, (int)(src_rows * h * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t dst_r = __builtin_amdgcn_make_buffer_rsrc(d_x, 0, (int)(T * h * 2), 0x00020000);
+    // the lane's 4 token rows of group tg (tokens tg .. tg + 15 of the workgroup) are tg + 4 g + v
+    auto load_rows = [&](int tg, u32x4(&dst)[4]) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                // operands swapped: the lane ends up with token row lane % 32 and 4 consecutive columns per quad
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh[j][kb], ah[kb], acc[j], 0, 0, 0);
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bl[j][kb], ah[kb], acc[j], 0, 0, 0);
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bh[j][kb], al[kb], acc[j], 0, 0, 0);
-            }
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int vq = 0; vq < 4; ++vq) {
-                const f32x4 v = {acc[j][vq * 4], acc[j][vq * 4 + 1], acc[j][vq * 4 + 2], acc[j][vq * 4 + 3]};
-                *(f32x4 *)&G[lane & 31][wave * 64 + j * 32 + vq * 8 + (lane >> 5) * 4] = v;
-            }
-        __syncthreads();
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int tt = (tid >> 5) + 8 * u;
-            if (!cin || tb + tt >= T) continue;
-            const f32x4 g0 = *(const f32x4 *)&G[tt][c8], g1 = *(const f32x4 *)&G[tt][c8 + 4];
-            const bf16x8 b = __builtin_bit_cast(bf16x8, rows[u]);
-            bf16x8 o;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                o[q] = f32_to_bf16(bf16_to_f32(b[q]) + g0[q]);
-                o[q + 4] = f32_to_bf16(bf16_to_f32(b[q + 4]) + g1[q]);
-            }
-            *(bf16x8 *)(d_x + (tb + tt) * h + c0 + c8) = o;
+        for (int v = 0; v < 4; ++v) {
+            const int32_t r = s_row[tg + 4 * g + v];
+            const uint32_t off = (cin & (r >= 0)) ? ((uint32_t)r * (uint32_t)h + (uint32_t)col) * 2u : OUTSIDE;
+            dst[v] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(src_r, off, 0, 0));
         }
     };
-    // number of this workgroup's tiles that hold tokens (uniform)
-    int ntile = tiles_per_wg;
-    if (t_first + (int64_t)ntile * TT > T) ntile = (int)((T - t_first + TT - 1) / TT);
-    load_rows(0, raw);
-    for (int it = 0; it < ntile; it += 2) {
-        load_rows(it + 1, nxt);
-        tile(it, raw);
-        load_rows(it + 2, raw);
-        if (it + 1 < ntile) tile(it + 1, nxt);
+    // The kernel is bound by memory latency, i.e. by the bytes each compute unit keeps in flight: row
+    // requests run two groups ahead of the arithmetic, in three register sets that rotate (the loop is
+    // unrolled, so no set is ever copied: a copy would wait for its load).
+    auto step = [&](int tg, const u32x4(&rows_cur)[4], u32x4(&rows_dst)[4]) {
+        load_rows(tg + 32, rows_dst);           // past the workgroup's tokens s_row holds -1: zero rows, never stored
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 ah[KS], al[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            // A operand: token tg + lane % 16, experts 32 ks + 8 g .. + 7
+            const int k0 = ks * 32 + 8 * g;
+            const bool kin = k0 < E8;
+            const float *p = &s_f[(tg + n16) * LDE + (kin ? k0 : 0)];
+            const f32x4 a0 = *(const f32x4 *)p, a1 = *(const f32x4 *)(p + 4);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const float a = kin ? (q < 4 ? a0[q & 3] : a1[q & 3]) : 0.f;
+                const bf16_t hq = f32_to_bf16(a);
+                ah[ks][q] = hq;
+                al[ks][q] = f32_to_bf16(a - bf16_to_f32(hq));
+            }
+        }
+        f32x4 acc[8];
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            acc[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[ks], bh[b][ks], acc[b], 0, 0, 0);
+                acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ah[ks], bl[b][ks], acc[b], 0, 0, 0);
+                acc[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(al[ks], bh[b][ks], acc[b], 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // result: lane holds token rows 4 g + v, column slot n16 of block b = column col + b
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int tt = tg + 4 * g + v;
+            const bf16x8 r = __builtin_bit_cast(bf16x8, rows_cur[v]);
+            bf16x8 o;
+#pragma unroll
+            for (int b = 0; b < 8; ++b) o[b] = f32_to_bf16(bf16_to_f32(r[b]) + acc[b][v]);
+            const uint32_t off = (cin & (tt < nt)) ? ((uint32_t)(t_begin + tt) * (uint32_t)h + (uint32_t)col) * 2u : OUTSIDE;
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(__attribute__((ext_vector_type(4))) unsigned int, o), dst_r, off, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    u32x4 r0[4], r1[4], r2[4];
+    load_rows(0, r0);
+    load_rows(16, r1);
+    // step k: rows in r[k % 3], the new requests go to r[(k + 2) % 3].  Every trip runs all three steps, also
+    // past the last token (zero rows, nothing stored): no branch, so the waits inside count exact loads.
+    static_assert(DX_TOKENS % 48 == 0, "three 16-token steps per trip");
+    // Fully unrolled: a loop back-edge makes the register allocator copy the rotating sets, and a copy of a
+    // register that a load is still writing is a full wait.
+#pragma unroll
+    for (int tg = 0; tg < DX_TOKENS; tg += 48) {
+        step(tg, r0, r2);
+        step(tg + 16, r1, r0);
+        step(tg + 32, r2, r1);
     }
 }
 
@@ -556,17 +580,38 @@ static void launch_dx(const moe_shape_t *sh, const float *w_gate, const float *d
                        sh->E, j0, chunk_len, (const bf16_t *)d_buf, expert, slot, sh->C);
 }
 
+// the matrix-core kernel keeps buffer row numbers in 32 bits
+// (and moves rows through buffer resources whose offsets must stay below 2^31)
+static bool dx_rows_ok(const moe_shape_t *sh) {
+    return sh->E <= 64 && (double)sh->E * (double)sh->C * sh->h * 2.0 < 2147483648.0 &&
+           (double)sh->T * sh->h * 2.0 < 2147483648.0;
+}
+
 static void launch_dx_mfma(const moe_shape_t *sh, const float *w_gate, const float *d_logits, void *d_x, hipStream_t s,
                            const void *d_buf = nullptr, const int32_t *expert = nullptr, const int32_t *slot = nullptr) {
-    const int tiles_per_wg = 8;                     // at most 8: the kernel keeps one gather row per thread (4 to 8 are equally fast)
-    dim3 grid((unsigned)((sh->h + 255) / 256), (unsigned)((sh->T + 32 * tiles_per_wg - 1) / (32 * tiles_per_wg)));
-#define MOE_DX_MFMA(KB)                                                                                                  \
-    hipLaunchKernelGGL((gate_dx_mfma_kernel<KB>), grid, dim3(256), 0, s, w_gate, d_logits, (bf16_t *)d_x, sh->T, sh->h, \
-                       sh->E, tiles_per_wg, (const bf16_t *)d_buf, expert, slot, sh->C)
-    if (sh->E <= 16) MOE_DX_MFMA(1);
-    else if (sh->E <= 32) MOE_DX_MFMA(2);
-    else MOE_DX_MFMA(4);
-#undef MOE_DX_MFMA
+    // a workgroup = 4 waves = 512 columns of one chunk of DX_TOKENS tokens; the chunk amortises the Wg^T
+    // fragments (128 columns x E floats per wave) and is short enough to give every compute unit several workgroups
+    dim3 grid((unsigned)((sh->h + 511) / 512), (unsigned)((sh->T + DX_TOKENS - 1) / DX_TOKENS));
+    const int E8 = (sh->E + 7) & ~7;
+    const size_t lds = (size_t)512 * (E8 + 4) * 4 + (DX_TOKENS + 48) * 4;       // 512 >= DX_TOKENS + 16 rows
+    static_assert(DX_TOKENS + 16 <= 512, "the d_logits rows reuse the 512-row region");
+    // more than 64 KB of dynamic LDS has to be allowed per kernel (E > 32: up to 139 KB)
+#define MOE_DX_ROWS(KS, GATHER)                                                                                      \
+    do {                                                                                                             \
+        if (lds > 65536)                                                                                             \
+            (void)hipFuncSetAttribute((const void *)gate_dx_rows_kernel<KS, GATHER>,                                 \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                        \
+        hipLaunchKernelGGL((gate_dx_rows_kernel<KS, GATHER>), grid, dim3(256), lds, s, w_gate, d_logits,             \
+                           (bf16_t *)d_x, sh->T, sh->h, sh->E, (const bf16_t *)d_buf, expert, slot, sh->C);          \
+    } while (0)
+    if (d_buf) {
+        if (sh->E <= 32) MOE_DX_ROWS(1, true);
+        else MOE_DX_ROWS(2, true);
+    } else {
+        if (sh->E <= 32) MOE_DX_ROWS(1, false);
+        else MOE_DX_ROWS(2, false);
+    }
+#undef MOE_DX_ROWS
 }
 
 moe_status_t run_gate_bwd(const moe_shape_t *sh, const float *d_gate_p, const float *probs, const int32_t *expert,
@@ -608,7 +653,7 @@ moe_status_t run_gate_bwd(const moe_shape_t *sh, const float *d_gate_p, const fl
                            d_w_gate, sh->h, E, Epad, nch);
     }
     if (d_x_accum) {
-        if (E <= 64) launch_dx_mfma(sh, w_gate, d_logits, d_x_accum, s);
+        if (dx_rows_ok(sh)) launch_dx_mfma(sh, w_gate, d_logits, d_x_accum, s);
         else
             for (int j0 = 0; j0 < E; j0 += 64) launch_dx<2, 64>(sh, w_gate, d_logits, d_x_accum, j0, s);
     }
@@ -640,7 +685,7 @@ moe_status_t run_dispatch_bwd_fused(const moe_shape_t *sh, const void *d_buf, co
                                     const int32_t *slot, void *d_x, const float *d_logits, const float *w_gate,
                                     hipStream_t s) {
     const int E = sh->E;
-    if (E <= 64) launch_dx_mfma(sh, w_gate, d_logits, d_x, s, d_buf, expert, slot);
+    if (dx_rows_ok(sh)) launch_dx_mfma(sh, w_gate, d_logits, d_x, s, d_buf, expert, slot);
     else {
         launch_dx<2, 64>(sh, w_gate, d_logits, d_x, 0, s, d_buf, expert, slot);
         for (int j0 = 64; j0 < E; j0 += 64) launch_dx<2, 64>(sh, w_gate, d_logits, d_x, j0, s);
