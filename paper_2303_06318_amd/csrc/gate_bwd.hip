@@ -109,31 +109,38 @@ __global__ void gate_dlogits_planes_kernel(const float *d_gate_p, const float *p
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4_g;
 
 // partial[chunk][e][col] = sum over the chunk's tokens of dL[t,e] * x[t,col]
+// The kernel streams x once and is bound by the bytes each compute unit keeps in flight: a workgroup has
+// the x tiles of the next two iterations (2 x 16 KB) and the d_logits fragments of the next iteration
+// requested while it multiplies.  Within an iteration the small requests (d_logits planes) are issued
+// before the x tile: the memory counter retires in issue order, so waiting for the planes of the next
+// iteration leaves the newer x tiles in flight.
 template <int NT>
 __global__ __launch_bounds__(256) void gate_dwg_mfma_kernel(const bf16_t *x, const bf16_t *planes, float *partial,
                                                              int64_t T, int h, int64_t Tpad, int64_t chunk_len,
                                                              int Epad) {
-    __shared__ __attribute__((aligned(16))) char xs[2][32 * 512];    // [32 tokens][256 cols] bf16, swizzled
+    __shared__ __attribute__((aligned(16))) char xs[3][32 * 512];    // [32 tokens][256 cols] bf16, swizzled
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c0 = blockIdx.x * 256;
     const int64_t t_begin = (int64_t)blockIdx.y * chunk_len;
     const int64_t t_end = t_begin + chunk_len < Tpad ? t_begin + chunk_len : Tpad;
     const int64_t plane = (int64_t)Epad * Tpad;      // distance between the hi / mid / lo planes
 
-    // loader: thread -> token rows tid/32 + 8q (q = 0..3), granule tid%32 (8 columns)
+    // loader: thread -> token rows tid/32 + 8q (q = 0..3), granule tid%32 (8 columns); rows past T and
+    // columns past h read as zero through the buffer resource (offset marker beyond its size)
     const int lg = tid & 31, lrow = tid >> 5;
     const bool col_ok = c0 + lg * 8 < h;
-    u32x4 stg[4];
-    auto gload = [&](int64_t t0) {
+    constexpr uint32_t OUTSIDE = 0x80000000u;
+    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t *>(x + t_begin * h), 0, (int)((T - t_begin < chunk_len ? T - t_begin : chunk_len) * h * 2), 0x00020000);
+    auto gload = [&](int64_t t0, u32x4(&stg)[4]) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const int64_t t = t0 + lrow + 8 * q;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (col_ok && t < T) v = *(const u32x4 *)(x + t * h + c0 + lg * 8);
-            stg[q] = v;
+            const int64_t tr = t0 - t_begin + lrow + 8 * q;         // row inside the chunk
+            const uint32_t off = (col_ok & (t0 + lrow + 8 * q < T)) ? ((uint32_t)tr * (uint32_t)h + c0 + lg * 8) * 2u : OUTSIDE;
+            stg[q] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(xr, off, 0, 0));
         }
     };
-    auto sstore = [&](int buf) {
+    auto sstore = [&](int buf, const u32x4(&stg)[4]) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int k = lrow + 8 * q;
@@ -154,16 +161,17 @@ __global__ __launch_bounds__(256) void gate_dwg_mfma_kernel(const bf16_t *x, con
     for (int et = 0; et < NT; ++et)
 #pragma unroll
         for (int nb = 0; nb < 4; ++nb) acc[et][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    if (t_begin < t_end) {
-        gload(t_begin);
-        sstore(0);
-    }
-    __syncthreads();
-    int buf = 0;
-    for (int64_t t0 = t_begin; t0 < t_end; t0 += 32) {
-        const bool more = t0 + 32 < t_end;
-        if (more) gload(t0 + 32);
+    // A fragments (d_logits planes, transposed: a lane's 8 consecutive tokens are 16 bytes), one iteration ahead
+    auto aload = [&](int64_t t0, u32x4(&av)[NT][3]) {
+        const int64_t ts = t0 < t_end ? t0 : t_begin;               // past the end: any valid tile (never used)
+#pragma unroll
+        for (int et = 0; et < NT; ++et)
+#pragma unroll
+            for (int p3 = 0; p3 < 3; ++p3)
+                av[et][p3] = *(const u32x4 *)(planes + p3 * plane + (int64_t)(et * 16 + (lane & 15)) * Tpad + ts +
+                                              8 * (lane >> 4));
+    };
+    auto compute = [&](int buf, const u32x4(&av)[NT][3]) {
         bf16x8 bfr[4];
 #pragma unroll
         for (int nb = 0; nb < 4; ++nb) {
@@ -177,16 +185,40 @@ __global__ __launch_bounds__(256) void gate_dwg_mfma_kernel(const bf16_t *x, con
         for (int et = 0; et < NT; ++et)
 #pragma unroll
             for (int p3 = 0; p3 < 3; ++p3) {
-                const u32x4 av = *(const u32x4 *)(planes + p3 * plane + (int64_t)(et * 16 + (lane & 15)) * Tpad + t0 +
-                                                  8 * (lane >> 4));
-                const bf16x8 a = __builtin_bit_cast(bf16x8, av);
+                const bf16x8 a = __builtin_bit_cast(bf16x8, av[et][p3]);
 #pragma unroll
                 for (int nb = 0; nb < 4; ++nb)
                     acc[et][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bfr[nb], acc[et][nb], 0, 0, 0);
             }
-        if (more) sstore(buf ^ 1);
+    };
+    // One iteration: tile i sits in xs[i % 3]; s_cur holds tile i + 1 (requested two iterations ago) and is
+    // stored to xs[(i + 1) % 3] after this tile's arithmetic; then tile i + 3 is requested into s_cur.  Two
+    // register sets alternate (the loop body is two iterations, so no set is ever copied).
+    auto iteration = [&](int64_t t0, int buf, const u32x4(&a_cur)[NT][3], u32x4(&a_nxt)[NT][3], u32x4(&s_cur)[4]) {
+        aload(t0 + 32, a_nxt);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(buf, a_cur);
+        sstore(buf == 2 ? 0 : buf + 1, s_cur);
+        __builtin_amdgcn_sched_barrier(0);
+        gload(t0 + 96, s_cur);                                      // past the chunk: zeros, never used
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
-        buf ^= 1;
+    };
+    u32x4 sA[4], sB[4], aA[NT][3], aB[NT][3];
+    if (t_begin < t_end) {
+        gload(t_begin, sA);
+        sstore(0, sA);
+        aload(t_begin, aA);
+        gload(t_begin + 32, sA);
+        gload(t_begin + 64, sB);
+    }
+    __syncthreads();
+    int buf = 0;
+    for (int64_t t0 = t_begin; t0 < t_end; t0 += 64) {
+        iteration(t0, buf, aA, aB, sA);
+        buf = buf == 2 ? 0 : buf + 1;
+        if (t0 + 32 < t_end) iteration(t0 + 32, buf, aB, aA, sB);
+        buf = buf == 2 ? 0 : buf + 1;
     }
     // result block: lane holds column lane%16, rows (experts) 4*(lane/16) + v
 #pragma unroll
@@ -556,8 +588,13 @@ static moe_status_t run_gate_bwd_simple(const moe_shape_t *sh, const float *d_ga
 // ---- workspace layout of the bf16 path: [planes 3*Epad*Tpad bf16][partial nchunks*Epad*h fp32]
 static int epad_of(int E) { return (E + 15) / 16 * 16; }
 static int64_t tpad_of(int64_t T) { return (T + 31) / 32 * 32; }
+// Token chunks of the d_w_gate kernel: enough workgroups (256-column blocks x chunks) for three per compute
+// unit of the 256-CU chip, chunks of at least 128 tokens, at most 64 partial results to sum.
 static int dwg_chunks(const moe_shape_t *sh) {
-    int64_t n = (tpad_of(sh->T) + 511) / 512;
+    const int64_t col_blocks = (sh->h + 255) / 256;
+    int64_t n = (768 + col_blocks - 1) / col_blocks;
+    const int64_t most = (tpad_of(sh->T) + 127) / 128;
+    if (n > most) n = most;
     return (int)(n < 1 ? 1 : (n > 64 ? 64 : n));
 }
 static size_t planes_bytes(const moe_shape_t *sh) {

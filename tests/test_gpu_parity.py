@@ -322,7 +322,10 @@ def test_activation_recomputation_gives_identical_bits(orc, name):
     sh = moe.make_shape(wl.T, wl.h, wl.E, wl.f, wl.C, moe.MOE_BF16 if wl.dtype == "bf16" else moe.MOE_F32)
     esz = 2 if wl.dtype == "bf16" else 4
     extra = moe.moe_workspace_bytes(sh, 2) - moe.moe_workspace_bytes(sh, 1)
-    assert 0 < extra <= 2 * (wl.E * wl.C * wl.f * esz + 256) + 65536
+    # one workspace serves every call of a layer, so the recomputing mode adds at most the two [E,C,f] arrays
+    # (nothing when another call's need, e.g. the gate backward's partial sums, is the larger one)
+    assert 0 <= extra <= 2 * (wl.E * wl.C * wl.f * esz + 256) + 65536
+    assert moe.moe_workspace_bytes(sh, 2) >= 3 * wl.E * wl.C * wl.f * esz
 
 
 @pytest.mark.parametrize("name", ["cfg2_small", "cfg3_small", "cfg4_small", "cfg5_small", "bf16_one_expert",

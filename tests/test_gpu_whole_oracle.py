@@ -1,5 +1,5 @@
-"""The benchmarked workload (6.7B-base shard, forward + backward, T=16384 h=4096 E=16 f=4096) against
-the WHOLE oracle, element-wise: every output and every saved intermediate is compared per row and per
+"""Every workload at its stated size against the WHOLE oracle.  First the benchmarked one (6.7B-base shard,
+forward + backward, T=16384 h=4096 E=16 f=4096), element-wise: every output and every saved intermediate is compared per row and per
 256 x 256 tile (not by one norm over the tensor), in the launch configuration bench.py times; then the
 same comparison for the fused forward (dispatch / combine folded into the GEMMs) with the recomputing
 backward.  The oracle pass takes about a minute of host time on the GPU machine's 16 cores."""
@@ -16,7 +16,7 @@ pytestmark = [pytest.mark.gpu, pytest.mark.timeout(1500)]
 
 
 def _progress(msg, t0):
-    print("[cfg5 whole oracle] %s (%.0f s)" % (msg, time.time() - t0), flush=True)
+    print("[whole oracle] %s (%.0f s)" % (msg, time.time() - t0), flush=True)
 
 
 def compare_with_oracle(orc, layer, inp, wl, fw, bw, what, t0):
@@ -100,3 +100,42 @@ def test_cfg5_every_row_and_tile_against_the_whole_oracle(orc):
     assert_close_everywhere("gathered forward out", host(fwd.out), fw["out"], 2e-2)
     assert_close_everywhere("gathered forward hact", kept_rows(host(fwd.hact), fw["kept"]), kept_rows(fw["H"], fw["kept"]), 2e-2)
     _progress("done", t0)
+
+
+@pytest.mark.parametrize("name", ["cfg2_1p3b_fwd", "cfg3_6p7b_tp4_fwd", "cfg4_skewed_fwd"])
+def test_forward_workloads_every_row_and_tile_against_the_whole_oracle(orc, name):
+    """The three forward workloads at full size: routing bit-exact, the dispatch copy bitwise, hact / y / out per
+    row, per 256 x 256 tile and per element against a full oracle pass (10-15 s of host time each), for the
+    three-call path and for the gathered / scattered fused forward."""
+    t0 = time.time()
+    wl = synth.WORKLOADS[name]
+    inp = synth.make_inputs(wl)
+    dev = DevInputs(inp)
+    layer = make_layer(wl)
+    layer.forward(dev.x, dev.wg, dev.w1, dev.w2, logit_bias=dev.bias)
+    torch.cuda.synchronize()
+    g_logits = host(layer.logits)
+    o_logits = orc.gate_logits(inp.x, inp.wg)
+    if inp.logit_bias is not None:
+        o_logits = (o_logits + inp.logit_bias[None, :]).astype(np.float32)
+    assert relfro(g_logits, o_logits) <= 1e-5
+    fw = orc.layer_forward(inp.x, inp.wg, inp.w1, inp.w2, wl.C, logits=g_logits)
+    _progress(name + ": oracle forward done", t0)
+    for a, b in ((layer.expert, "expert"), (layer.slot, "slot"), (layer.counts, "counts"), (layer.kept, "kept"),
+                 (layer.token_of_slot, "token_of_slot")):
+        assert np.array_equal(host(a), fw[b]), b
+    kept = fw["kept"]
+    assert np.abs(host(layer.gate_p) - fw["gate_p"]).max() <= 1e-5
+    assert np.array_equal(kept_rows(host(layer.buf), kept), kept_rows(fw["D"], kept))
+    if wl.zipf_bias:
+        assert (fw["slot"] < 0).sum() > wl.T // 4 and (kept == 0).any()
+    fused = make_layer(wl)
+    fused.forward(dev.x, dev.wg, dev.w1, dev.w2, logit_bias=dev.bias, fused=True)
+    torch.cuda.synchronize()
+    for what, L in (("three-call path", layer), ("fused forward", fused)):
+        assert_close_everywhere("%s %s hact" % (name, what), kept_rows(host(L.hact), kept), kept_rows(fw["H"], kept), 2e-2)
+        if L is layer:
+            assert_close_everywhere("%s %s y" % (name, what), kept_rows(host(L.y), kept), kept_rows(fw["Y"], kept), 2e-2)
+        assert_close_everywhere("%s %s out" % (name, what), host(L.out), fw["out"], 2e-2)
+        assert (host(L.out)[fw["slot"] < 0] == 0).all()
+    _progress(name + ": done", t0)
