@@ -35,7 +35,9 @@
  * Pins: see tests/test_oracle_*.py (brute force routing, one-hot cumsum
  * formulation, library matmul/softmax/GeLU in fp64, autograd through a dense
  * one-hot formulation, finite differences, the paper's 4-token example; for the optimizer step at
- * the end of this file: a library AdamW in fp64, closed forms of the first step, tiling invariance).
+ * the end of this file: a library AdamW in fp64, closed forms of the first step, tiling invariance;
+ * for duplicate token dropping: strided array slices, the round trip, every row in exactly one share,
+ * and the two-rank picture of the paper's Figure 5).
  */
 #include <math.h>
 #include <stdint.h>
@@ -132,6 +134,34 @@ void orc_dispatch(int64_t T, int32_t h, int32_t E, int64_t C, const float *x, co
         float *dst = D + ((int64_t)expert[t] * C + slot[t]) * h;
         for (int32_t k = 0; k < h; ++k) dst[k] = x[t * h + k];
     }
+}
+
+/* Duplicate token dropping (paper Section 5.1, Figure 5).  The G ranks of a tensor-parallel group hold the same
+ * expert chunks; before the all-to-all each rank "drops" all rows but its own share, so that every row
+ * leaves the group exactly once and the messages shrink by the factor G; after the all-to-all an all-gather
+ * among the G ranks puts the shares together again.  The paper does not say which rows a rank keeps; the
+ * reading here: rank r keeps rows s with s mod G == r, in order (row s becomes row s / G of its share).
+ *   drop:    share[e, j, :] = buf[e, j*G + r, :]   for j*G + r < C, zero rows beyond   (share is [E, Cg, w], Cg = ceil(C/G))
+ *   gather:  buf[e, s, :]   = shares[s mod G][e, s / G, :]                              (shares is [G, E, Cg, w])
+ * Works on float arrays of row width w (activations or their gradients: the backward swaps the two steps). */
+void orc_dtd_drop(int32_t E, int64_t C, int32_t w, int32_t G, int32_t r, const float *buf, float *share) {
+    const int64_t Cg = (C + G - 1) / G;
+    for (int32_t e = 0; e < E; ++e)
+        for (int64_t j = 0; j < Cg; ++j) {
+            const int64_t s = j * G + r;
+            float *dst = share + ((int64_t)e * Cg + j) * w;
+            for (int32_t k = 0; k < w; ++k) dst[k] = s < C ? buf[((int64_t)e * C + s) * w + k] : 0.0f;
+        }
+}
+
+void orc_dtd_gather(int32_t E, int64_t C, int32_t w, int32_t G, const float *shares, float *buf) {
+    const int64_t Cg = (C + G - 1) / G;
+    for (int32_t e = 0; e < E; ++e)
+        for (int64_t s = 0; s < C; ++s) {
+            const float *src = shares + (((int64_t)(s % G) * E + e) * Cg + s / G) * w;
+            float *dst = buf + ((int64_t)e * C + s) * w;
+            for (int32_t k = 0; k < w; ++k) dst[k] = src[k];
+        }
 }
 
 /* One expert's FFN on `rows` rows: Z = D W1, H = act(Z), Y = H W2.

@@ -74,6 +74,10 @@ def lib():
         L.orc_top1_softmax.argtypes = [i64, i32, p, p, p, p]
         L.orc_route.argtypes = [i64, i32, i64, p, p, p, p, p]
         L.orc_dispatch.argtypes = [i64, i32, i32, i64, p, p, p, p]
+        L.orc_dtd_drop.restype = None
+        L.orc_dtd_drop.argtypes = [i32, i64, i32, i32, i32, p, p]
+        L.orc_dtd_gather.restype = None
+        L.orc_dtd_gather.argtypes = [i32, i64, i32, i32, p, p]
         L.orc_ffn_fwd.argtypes = [i64, i32, i32, i32, p, p, p, p, p, p]
         L.orc_combine.argtypes = [i64, i32, i64, p, p, p, p, p]
         L.orc_combine_bwd.argtypes = [i64, i32, i32, i64, p, p, p, p, p, p, p]
@@ -156,6 +160,26 @@ def dispatch(x, expert, slot, E: int, Cap: int):
     D = np.empty((E, Cap, h), np.float32)
     lib().orc_dispatch(T, h, E, Cap, _p(x), _p(_a(expert, np.int32)), _p(_a(slot, np.int32)), _p(D))
     return D
+
+
+def dtd_drop(buf, G: int, r: int):
+    """Duplicate token dropping, the drop of rank r in a tensor-parallel group of G (paper Section 5.1):
+    buf [E, C, w] -> share [E, ceil(C/G), w] holding rows r, r+G, r+2G, ... of every expert, zero beyond C."""
+    buf = _a(buf, np.float32)
+    E, Cap, w = buf.shape
+    share = np.empty((E, (Cap + G - 1) // G, w), np.float32)
+    lib().orc_dtd_drop(E, Cap, w, G, r, _p(buf), _p(share))
+    return share
+
+
+def dtd_gather(shares, Cap: int):
+    """The all-gather's result put back in row order: shares [G, E, ceil(C/G), w] -> buf [E, C, w]."""
+    shares = _a(shares, np.float32)
+    G, E, Cg, w = shares.shape
+    assert Cg == (Cap + G - 1) // G
+    buf = np.empty((E, Cap, w), np.float32)
+    lib().orc_dtd_gather(E, Cap, w, G, _p(shares), _p(buf))
+    return buf
 
 
 def ffn_fwd(D_e, W1_e, W2_e, mode: int = ACT_GELU_ERF):

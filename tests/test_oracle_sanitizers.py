@@ -8,7 +8,8 @@ import sys
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-PIN_FILES = ["tests/test_oracle_routing.py", "tests/test_oracle_numerics.py", "tests/test_oracle_adamw.py"]
+PIN_FILES = ["tests/test_oracle_routing.py", "tests/test_oracle_numerics.py", "tests/test_oracle_adamw.py",
+             "tests/test_oracle_dtd.py"]
 
 
 @pytest.mark.skipif(os.environ.get("MOE_ORACLE_SANITIZE") == "1", reason="already inside the sanitized run")
