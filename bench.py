@@ -122,6 +122,9 @@ def main() -> int:
                     help="dispatch folded into GEMM1's operand load (forward-only workloads) and combine into GEMM2's "
                          "epilogue (moe_expert_ffn_fwd_fused)")
     ap.add_argument("--tile-size", type=int, default=1_800_000, help="ts of the tiled optimizer step")
+    ap.add_argument("--dtd", type=int, default=0, metavar="G",
+                    help="also time the local halves of duplicate token dropping for a tensor-parallel group of G "
+                         "(reported in an extra \"dtd\" object; never part of ms_per_step)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU's share of the layer on ONE GPU; --gpus must be 1 "
@@ -309,6 +312,34 @@ def main() -> int:
                                   f"({'fwd+bwd' if wl.backward else 'fwd'}, all {wl.E} experts, capacity {Cs}), "
                                   f"{tc1 - tc0:.1f} s"}
 
+    dtd = None
+    if args.dtd > 1:
+        # One rank's drop fused with dispatch (1/G of the rows), the expert FFN reading all G shares in place, the
+        # reassembling copy, and for a training step the backward's drop and the dispatch backward from shares.
+        G = args.dtd
+        Cg = -(-wl.C // G)
+        shares = torch.empty((G, wl.E, Cg, wl.h), dtype=torch.bfloat16, device="cuda")
+        for r in range(G):
+            moe.moe_dispatch_dtd(sh, x, layer.token_of_slot, r, G, shares[r])
+        dtd = {"tp_size": G, "share_rows_per_expert": Cg,
+               "dispatch_dtd_one_rank_us": round(timed_us(lambda: moe.moe_dispatch_dtd(sh, x, layer.token_of_slot, 0, G, shares[0])), 2),
+               "dispatch_whole_chunks_us": round(timed_us(lambda: moe.moe_dispatch(sh, x, layer.token_of_slot, layer.buf)), 2),
+               "ffn_fwd_from_shares_us": round(timed_us(lambda: moe.moe_expert_ffn_fwd_dtd(
+                   sh, shares, G, w1, w2, layer.kept, layer.z_save, layer.hact, layer.y, layer.ws), 10), 2),
+               "ffn_fwd_from_chunks_us": round(timed_us(lambda: moe.moe_expert_ffn_fwd(
+                   sh, layer.buf, w1, w2, layer.kept, layer.z_save, layer.hact, layer.y, layer.ws), 10), 2),
+               "gather_copy_us": round(timed_us(lambda: moe.moe_dtd_gather(sh, shares, layer.kept, G, layer.buf)), 2)}
+        if wl.backward:
+            d_shares = torch.empty_like(shares)
+            for r in range(G):
+                moe.moe_dtd_drop(sh, layer.d_buf, layer.kept, r, G, d_shares[r])
+            dtd["drop_d_buf_one_rank_us"] = round(timed_us(lambda: moe.moe_dtd_drop(sh, layer.d_buf, layer.kept, 0, G, d_shares[0])), 2)
+            dtd["dispatch_bwd_from_shares_us"] = round(timed_us(lambda: moe.moe_dispatch_bwd_dtd(
+                sh, d_shares, G, layer.expert, layer.slot, layer.d_x, layer.d_logits, wg)), 2)
+            dtd["dispatch_bwd_from_chunks_us"] = round(timed_us(lambda: moe.moe_dispatch_bwd(
+                sh, layer.d_buf, layer.expert, layer.slot, layer.d_x, layer.d_logits, wg)), 2)
+        del shares
+
     optimizer = None
     if args.optimizer:
         optimizer = bench_optimizer(args, wl, layer, w1, w2)
@@ -345,6 +376,8 @@ def main() -> int:
     }
     if optimizer is not None:
         out["optimizer"] = optimizer
+    if dtd is not None:
+        out["dtd"] = dtd
     print(json.dumps(out))
     return 0
 

@@ -210,6 +210,64 @@ moe_status_t moe_expert_ffn_fwd_fused(const moe_shape_t *shape, const void *x, c
                                       const void *w1, const void *w2, const int32_t *kept, void *z_save, void *hact,
                                       void *y, void *out, void *ws, size_t ws_bytes, void *stream);
 
+/* ---- duplicate token dropping (Section 5.1, Figure 5), the local halves ----
+ *
+ * The G = tp_size GPUs of a tensor-parallel group hold identical expert chunks before the first
+ * all-to-all.  Each performs a "drop" that leaves it a share of the rows, disjoint from the other
+ * ranks' shares, so the all-to-all messages shrink by the factor G; after the all-to-all an all-gather
+ * inside the group reassembles the chunks.  In the backward pass the two steps change places.  The paper
+ * does not fix which rows a rank keeps; this library's convention: rank r keeps rows s with s mod G = r
+ * of every expert chunk, in order, so row s of a chunk is row s / G of share s mod G.  A share is
+ * [E, Cg, h] with Cg = ceil(C / G); shares of all ranks, as the all-gather delivers them, are
+ * [G, E, Cg, h].  Rows that correspond to empty slots (s >= kept[e]) are never written and never read.
+ * Requirements for all five calls: 1 <= tp_size <= C, 0 <= tp_rank < tp_size.
+ */
+
+/*
+ * Dispatch fused with the drop of rank tp_rank (Figure 5, step 1, on top of Section 3, step 4):
+ *   share[e, j, :] = x[token_of_slot[e, j * tp_size + tp_rank], :]   for filled slots.
+ *   x [T,h], token_of_slot [E,C], share [E,Cg,h] (out).
+ */
+moe_status_t moe_dispatch_dtd(const moe_shape_t *shape, const void *x, const int32_t *token_of_slot, int32_t tp_rank,
+                              int32_t tp_size, void *share, void *stream);
+
+/*
+ * The drop alone, for any [E,C,h] row array (the backward pass drops d_buf before the reverse all-to-all):
+ *   share[e, j, :] = buf[e, j * tp_size + tp_rank, :]   for j * tp_size + tp_rank < kept[e].
+ */
+moe_status_t moe_dtd_drop(const moe_shape_t *shape, const void *buf, const int32_t *kept, int32_t tp_rank,
+                          int32_t tp_size, void *share, void *stream);
+
+/*
+ * The all-gathered shares put back in row order (Figure 5, step 2, local half), as a copy:
+ *   buf[e, s, :] = shares[s mod tp_size][e, s / tp_size, :]   for s < kept[e].
+ * A training step needs this array (the weight gradient reads the dispatched rows along its reduction
+ * index); a forward-only layer does not: moe_expert_ffn_fwd_dtd reads the shares in place.
+ *   shares [G,E,Cg,h], kept [E], buf [E,C,h] (out).
+ */
+moe_status_t moe_dtd_gather(const moe_shape_t *shape, const void *shares, const int32_t *kept, int32_t tp_size,
+                            void *buf, void *stream);
+
+/*
+ * moe_expert_ffn_fwd whose first GEMM takes row s of expert e straight from shares[s mod G][e, s / G, :]
+ * (the strided form of the gathered operand load of moe_expert_ffn_fwd_fused): no reassembled copy of the
+ * chunks is written or read.  bf16 only; G*E*Cg*h*2 < 2^31.  Results are bit-identical to
+ * moe_dtd_gather + moe_expert_ffn_fwd.  Other arguments and workspace as for moe_expert_ffn_fwd.
+ */
+moe_status_t moe_expert_ffn_fwd_dtd(const moe_shape_t *shape, const void *shares, int32_t tp_size, const void *w1,
+                                    const void *w2, const int32_t *kept, void *z_save, void *hact, void *y, void *ws,
+                                    size_t ws_bytes, void *stream);
+
+/*
+ * moe_dispatch_bwd reading the all-gathered gradient shares (backward of Figure 5: the drop of d_buf by
+ * moe_dtd_drop, the reverse all-to-all, then an all-gather) in place:
+ *   d_x[t,:] = d_shares[slot[t] mod G][expert[t], slot[t] / G, :] if slot[t] >= 0 else 0   (+ d_logits[t,:] w_gate^T).
+ *   d_shares [G,E,Cg,h]; the other arguments as for moe_dispatch_bwd.
+ */
+moe_status_t moe_dispatch_bwd_dtd(const moe_shape_t *shape, const void *d_shares, int32_t tp_size,
+                                  const int32_t *expert, const int32_t *slot, void *d_x, const float *d_logits,
+                                  const float *w_gate, void *stream);
+
 /* ---- backward (end of Section 3: the same steps in reverse order) ---- */
 
 /*

@@ -262,7 +262,7 @@ __global__ void gate_dwg_reduce_t_kernel(const float *partial, float *d_w_gate, 
 template <int CW, int EJ>
 __global__ __launch_bounds__(256) void gate_dx_kernel(const float *w_gate, const float *d_logits, bf16_t *d_x, int64_t T,
                                                        int h, int E, int j0, int64_t chunk_len, const bf16_t *d_buf,
-                                                       const int32_t *expert, const int32_t *slot, int64_t C) {
+                                                       const int32_t *expert, const int32_t *slot, int64_t Cg, int G) {
     constexpr int TT = 64;
     __shared__ float dl[TT][EJ];
     __shared__ int32_t srow[TT];      // fused gather: buffer row of each token, -1 if dropped
@@ -284,7 +284,7 @@ __global__ __launch_bounds__(256) void gate_dx_kernel(const float *w_gate, const
         }
         if (d_buf && tid < TT && tb + tid < t_end) {
             const int sl = slot[tb + tid];
-            srow[tid] = sl < 0 ? -1 : (int32_t)((int64_t)expert[tb + tid] * C + sl);
+            srow[tid] = sl < 0 ? -1 : (int32_t)(((int64_t)(sl % G) * E + expert[tb + tid]) * Cg + sl / G);
         }
         __syncthreads();
         const int nt = (int)(t_end - tb < TT ? t_end - tb : TT);
@@ -385,7 +385,9 @@ constexpr int DX_TOKENS = 192;          // tokens per workgroup (4 waves x 128 c
 template <int KS, bool GATHER>          // 32-expert k-steps (E <= 32 KS); rows gathered from d_buf, or d_x in place
 __global__ __launch_bounds__(256, KS == 1 ? 2 : 1) void gate_dx_rows_kernel(
     const float *w_gate, const float *d_logits, bf16_t *d_x, int64_t T, int h, int E, const bf16_t *d_buf,
-    const int32_t *expert, const int32_t *slot, int64_t C) {
+    const int32_t *expert, const int32_t *slot, int64_t Cg, int G) {
+    // d_buf is [E, C, h], or (duplicate token dropping, G > 1) the G shares [G, E, Cg, h]: row s of expert e
+    // is row s / G of share s % G; G = 1, Cg = C is the plain layout
     // One dynamic LDS region of 512 rows x (E8 + 4) floats (E8 = E rounded up to 8), used twice: first the
     // workgroup's 512 rows of Wg, read from memory with coalesced accesses and then picked apart into MFMA
     // fragments; afterwards the d_logits rows of its tokens.  Behind it, the source row of every token.
@@ -422,7 +424,7 @@ __global__ __launch_bounds__(256, KS == 1 ? 2 : 1) void gate_dx_rows_kernel(
         int32_t r = (int32_t)t;
         if (GATHER) {
             const int sl = slot[t], ex = expert[t];
-            r = sl >= 0 ? ex * (int32_t)C + sl : -1;
+            r = sl >= 0 ? ((sl % G) * E + ex) * (int32_t)Cg + sl / G : -1;
         }
         s_row[i] = tin ? r : -1;
     }
@@ -463,7 +465,7 @@ __global__ __launch_bounds__(256, KS == 1 ? 2 : 1) void gate_dx_rows_kernel(
     // dropped token, a token past the end, a column past h) makes a load return zeros and a store do nothing,
     // so the stream has no branches and the compiler's wait counts are exact.
     constexpr uint32_t OUTSIDE = 0x80000000u;                      // the host checks that both arrays are shorter
-    const int64_t src_rows = GATHER ? (int64_t)E * C : T;
+    const int64_t src_rows = GATHER ? (int64_t)G * E * Cg : T;
     const __amdgpu_buffer_rsrc_t src_r = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16_t *>(GATHER ? d_buf : d_x), 0, (int)(src_rows * h * 2), 0x00020000);
     const __amdgpu_buffer_rsrc_t dst_r = __builtin_amdgcn_make_buffer_rsrc(d_x, 0, (int)(T * h * 2), 0x00020000);
@@ -610,22 +612,23 @@ size_t gate_bwd_ws_bytes(const moe_shape_t *sh) {
 template <int CW, int EJ>
 static void launch_dx(const moe_shape_t *sh, const float *w_gate, const float *d_logits, void *d_x, int j0,
                       hipStream_t s, const void *d_buf = nullptr, const int32_t *expert = nullptr,
-                      const int32_t *slot = nullptr) {
+                      const int32_t *slot = nullptr, int tp_size = 1) {
     const int64_t chunk_len = 64;
     dim3 grid((unsigned)((sh->h + 256 * CW - 1) / (256 * CW)), (unsigned)((sh->T + chunk_len - 1) / chunk_len));
     hipLaunchKernelGGL((gate_dx_kernel<CW, EJ>), grid, dim3(256), 0, s, w_gate, d_logits, (bf16_t *)d_x, sh->T, sh->h,
-                       sh->E, j0, chunk_len, (const bf16_t *)d_buf, expert, slot, sh->C);
+                       sh->E, j0, chunk_len, (const bf16_t *)d_buf, expert, slot, (sh->C + tp_size - 1) / tp_size, tp_size);
 }
 
 // the matrix-core kernel keeps buffer row numbers in 32 bits
 // (and moves rows through buffer resources whose offsets must stay below 2^31)
-static bool dx_rows_ok(const moe_shape_t *sh) {
-    return sh->E <= 64 && (double)sh->E * (double)sh->C * sh->h * 2.0 < 2147483648.0 &&
-           (double)sh->T * sh->h * 2.0 < 2147483648.0;
+static bool dx_rows_ok(const moe_shape_t *sh, int tp_size = 1) {
+    const double src_rows = (double)tp_size * sh->E * (double)((sh->C + tp_size - 1) / tp_size);
+    return sh->E <= 64 && src_rows * sh->h * 2.0 < 2147483648.0 && (double)sh->T * sh->h * 2.0 < 2147483648.0;
 }
 
 static void launch_dx_mfma(const moe_shape_t *sh, const float *w_gate, const float *d_logits, void *d_x, hipStream_t s,
-                           const void *d_buf = nullptr, const int32_t *expert = nullptr, const int32_t *slot = nullptr) {
+                           const void *d_buf = nullptr, const int32_t *expert = nullptr, const int32_t *slot = nullptr,
+                           int tp_size = 1) {
     // a workgroup = 4 waves = 512 columns of one chunk of DX_TOKENS tokens; the chunk amortises the Wg^T
     // fragments (128 columns x E floats per wave) and is short enough to give every compute unit several workgroups
     dim3 grid((unsigned)((sh->h + 511) / 512), (unsigned)((sh->T + DX_TOKENS - 1) / DX_TOKENS));
@@ -639,7 +642,8 @@ static void launch_dx_mfma(const moe_shape_t *sh, const float *w_gate, const flo
             (void)hipFuncSetAttribute((const void *)gate_dx_rows_kernel<KS, GATHER>,                                 \
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                        \
         hipLaunchKernelGGL((gate_dx_rows_kernel<KS, GATHER>), grid, dim3(256), lds, s, w_gate, d_logits,             \
-                           (bf16_t *)d_x, sh->T, sh->h, sh->E, (const bf16_t *)d_buf, expert, slot, sh->C);          \
+                           (bf16_t *)d_x, sh->T, sh->h, sh->E, (const bf16_t *)d_buf, expert, slot,                  \
+                           (sh->C + tp_size - 1) / tp_size, tp_size);                                                \
     } while (0)
     if (d_buf) {
         if (sh->E <= 32) MOE_DX_ROWS(1, true);
@@ -720,11 +724,11 @@ moe_status_t run_gate_dx_f32(const moe_shape_t *sh, const float *d_logits, const
 //   d_x[t,:] = d_buf[expert[t], slot[t], :] (or 0) + d_logits[t,:] w_gate^T
 moe_status_t run_dispatch_bwd_fused(const moe_shape_t *sh, const void *d_buf, const int32_t *expert,
                                     const int32_t *slot, void *d_x, const float *d_logits, const float *w_gate,
-                                    hipStream_t s) {
+                                    hipStream_t s, int tp_size) {
     const int E = sh->E;
-    if (dx_rows_ok(sh)) launch_dx_mfma(sh, w_gate, d_logits, d_x, s, d_buf, expert, slot);
+    if (dx_rows_ok(sh, tp_size)) launch_dx_mfma(sh, w_gate, d_logits, d_x, s, d_buf, expert, slot, tp_size);
     else {
-        launch_dx<2, 64>(sh, w_gate, d_logits, d_x, 0, s, d_buf, expert, slot);
+        launch_dx<2, 64>(sh, w_gate, d_logits, d_x, 0, s, d_buf, expert, slot, tp_size);
         for (int j0 = 64; j0 < E; j0 += 64) launch_dx<2, 64>(sh, w_gate, d_logits, d_x, j0, s);
     }
     return check_launch("dispatch_bwd_fused");

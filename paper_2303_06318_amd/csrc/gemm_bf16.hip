@@ -118,11 +118,21 @@ struct Loader {
     int32_t kthr[CPW];    // the granule is inside K for k-tile origin k0 iff k0 < kthr
 };
 
-// `index` (KC operands only): row gx of the operand is row index[gx] of the array the resource covers
-// (negative: no such row).
+// Where row gx of a KC operand lives in the array its resource covers, when that is not row gx itself:
+// through an index array (negative entry: no such row), or in the row shares of duplicate token dropping
+// (share gx % G, row base + gx / G of that share).
+struct RowMap {
+    const int32_t *index;
+    int32_t G, share_rows, base;          // G > 0: shares of share_rows rows each; base = first row of this expert in a share
+    __device__ __forceinline__ bool mapped() const { return index != nullptr || G > 0; }
+    __device__ __forceinline__ int row(int gx) const {
+        return index != nullptr ? index[gx] : (gx % G) * share_rows + base + gx / G;
+    }
+};
+
 template <bool XC>
 __device__ __forceinline__ void loader_init(Loader &L, int ld, int x0, int xlim, int klim, int wave, int lane,
-                                            const int32_t *index = nullptr) {
+                                            const RowMap &map = RowMap{nullptr, 0, 0, 0}) {
 #pragma unroll
     for (int q = 0; q < CPW; ++q) {
         const int chunk = wave * CPW + q;
@@ -136,8 +146,8 @@ __device__ __forceinline__ void loader_init(Loader &L, int ld, int x0, int xlim,
             const int row = chunk * (1024 / KC_ROW) + lane / KC_G;
             const int g = (lane % KC_G) ^ ((row >> KC_SWZ_SHIFT) & (KC_G - 1));
             const int gx = x0 + row;
-            if (index != nullptr) {
-                const int src = gx < xlim ? index[gx] : -1;
+            if (map.mapped()) {
+                const int src = gx < xlim ? map.row(gx) : -1;
                 L.off[q] = src >= 0 ? ((uint32_t)src * ld + g * 8) * 2u : OOB;
             } else {
                 L.off[q] = gx < xlim ? ((uint32_t)gx * ld + g * 8) * 2u : OOB;
@@ -417,8 +427,12 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
     const int m0 = blk0 * 32, n0 = nti * BN;
     const int mlim = Me < m0 + nblk * 32 ? Me : m0 + nblk * 32;     // rows [m0, mlim) are this tile's
 
-    // gathered A (dispatch folded in): one array for all experts, rows through this expert's index slice
-    const int32_t *a_index = (!AXC && d.a_index != nullptr) ? d.a_index + (int64_t)e * d.M : nullptr;
+    // gathered A (dispatch folded in, or the row shares of duplicate token dropping): one array for all
+    // experts, rows through this expert's index slice or the share arithmetic
+    RowMap amap = {nullptr, 0, 0, 0};
+    if (!AXC && d.a_index != nullptr) amap.index = d.a_index + (int64_t)e * d.M;
+    else if (!AXC && d.a_dtd_g > 1) { amap.G = d.a_dtd_g; amap.share_rows = d.E * d.a_dtd_cg; amap.base = e * d.a_dtd_cg; }
+    const bool a_index = amap.mapped();
     const bf16_t *Ap = a_index ? (const bf16_t *)d.A : (const bf16_t *)d.A + (int64_t)e * d.strideA;
     const bf16_t *Bp = (const bf16_t *)d.B + (int64_t)e * d.strideB;
     // extent of this expert's operands in bytes (rows x row length)
@@ -455,7 +469,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
     // (a0/b0, a1/b1), all read in the memory phase that precedes the tile's 16 MFMAs.
     bf16x8 a0[4], b0[2], a1[4], b1[2], ax0, ax1, bx0, bx1;
     Loader la, lb;
-    loader_init<AXC>(la, d.lda, m0, mlim, Ke, wave, lane, a_index);
+    loader_init<AXC>(la, d.lda, m0, mlim, Ke, wave, lane, amap);
     loader_init<BXC>(lb, d.ldb, n0, d.N, Ke, wave, lane);
     // tall tile: the two 1 KB chunks of rows 256..287 are loaded by waves 0 and 5 (one wave of each
     // ping-pong group, on different SIMDs), which therefore have 5 loads per k-tile in flight
@@ -467,8 +481,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmDesc d) {
         const int row = 256 + 16 * xw + (lane >> 2);
         const int g = (lane & 3) ^ ((row >> KC_SWZ_SHIFT) & (KC_G - 1));
         const int gx = m0 + row;
-        if (a_index != nullptr) {
-            const int src = gx < mlim ? a_index[gx] : -1;
+        if (a_index) {
+            const int src = gx < mlim ? amap.row(gx) : -1;
             offx = src >= 0 ? ((uint32_t)src * d.lda + g * 8) * 2u : OOB;
         } else {
             offx = gx < mlim ? ((uint32_t)gx * d.lda + g * 8) * 2u : OOB;

@@ -33,7 +33,10 @@ moe_status_t run_gate(const moe_shape_t *, const void *, const float *, const fl
                       float *, int32_t *, int32_t *, int32_t *, int32_t *, void *, hipStream_t);
 moe_status_t run_dispatch(const moe_shape_t *, const void *, const int32_t *, void *, hipStream_t);
 moe_status_t run_dispatch_bwd(const moe_shape_t *, const void *, const int32_t *, const int32_t *, void *,
-                              hipStream_t);
+                              hipStream_t, int tp_size = 1);
+moe_status_t run_dispatch_dtd(const moe_shape_t *, const void *, const int32_t *, int, int, void *, hipStream_t);
+moe_status_t run_dtd_drop(const moe_shape_t *, const void *, const int32_t *, int, int, void *, hipStream_t);
+moe_status_t run_dtd_gather(const moe_shape_t *, const void *, const int32_t *, int, void *, hipStream_t);
 moe_status_t run_combine(const moe_shape_t *, const void *, const int32_t *, const int32_t *, const float *, void *,
                          hipStream_t);
 moe_status_t run_combine_prep(const moe_shape_t *, const int32_t *, const int32_t *, const float *, float *, void *,
@@ -43,7 +46,7 @@ moe_status_t run_combine_bwd(const moe_shape_t *, const void *, const void *, co
 moe_status_t run_gate_bwd(const moe_shape_t *, const float *, const float *, const int32_t *, const void *,
                           const float *, float *, float *, void *, void *, hipStream_t);
 moe_status_t run_dispatch_bwd_fused(const moe_shape_t *, const void *, const int32_t *, const int32_t *, void *,
-                                    const float *, const float *, hipStream_t);
+                                    const float *, const float *, hipStream_t, int tp_size = 1);
 struct AdamwConst {
     float lr, beta1, beta2, omb1, omb2, eps, wd, inv_bc1, inv_bc2, grad_mult;
 };
@@ -266,13 +269,19 @@ static moe_status_t check_ws(const char *fn, const void *ws, size_t have, size_t
 
 // The two forward GEMMs (arguments already validated; hact is a real array; `plans` holds
 // ffn_plan_bytes(G_FWD1..G_FWD2) bytes on the bf16 path and is unused on the fp32 path).
+// tp_size > 1: `buf` holds the tp_size row shares of duplicate token dropping, [G, E, ceil(C/G), h] (bf16 only).
 static moe_status_t ffn_fwd_launch(const moe_shape_t &s, const void *buf, const void *w1, const void *w2,
                                    const int32_t *kept, void *z_save, void *hact, void *y, char *plans,
-                                   hipStream_t hs) {
+                                   hipStream_t hs, int tp_size = 1) {
     const bool bf = s.dtype == MOE_BF16;
     moe_status_t st;
     GemmDesc g[2] = {ffn_gemm(s, G_FWD1), ffn_gemm(s, G_FWD2)};
     g[0].A = buf; g[0].B = w1; g[0].C = hact; g[0].C2 = z_save; g[0].kept = kept;
+    if (tp_size > 1) {
+        g[0].a_dtd_g = tp_size;
+        g[0].a_dtd_cg = (int32_t)((s.C + tp_size - 1) / tp_size);
+        g[0].a_rows = (int64_t)tp_size * s.E * g[0].a_dtd_cg;
+    }
     g[1].A = hact; g[1].B = w2; g[1].C = y; g[1].kept = kept;
     if (bf) {
         char *pl = plans;
@@ -461,6 +470,103 @@ moe_status_t moe_expert_ffn_fwd_fused(const moe_shape_t *shape, const void *x, c
     for (int i = 0; i < 2; ++i)
         if ((st = launch_gemm_bf16(g[i], hs)) != MOE_OK) return st;
     return MOE_OK;
+}
+
+static moe_status_t check_tp(const char *fn, const moe_shape_t *sh, int32_t tp_rank, int32_t tp_size) {
+    if (tp_size < 1 || tp_rank < 0 || tp_rank >= tp_size || (int64_t)tp_size > sh->C) {
+        set_error("%s: tp_rank=%d tp_size=%d (need 1 <= tp_size <= C = %lld and 0 <= tp_rank < tp_size)", fn, tp_rank,
+                  tp_size, (long long)sh->C);
+        return MOE_ERR_INVALID_ARG;
+    }
+    return MOE_OK;
+}
+
+moe_status_t moe_dispatch_dtd(const moe_shape_t *shape, const void *x, const int32_t *token_of_slot, int32_t tp_rank,
+                              int32_t tp_size, void *share, void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if ((st = check_tp("moe_dispatch_dtd", shape, tp_rank, tp_size)) != MOE_OK) return st;
+    REQUIRE_PTR(x);
+    REQUIRE_PTR(token_of_slot);
+    REQUIRE_PTR(share);
+    return run_dispatch_dtd(shape, x, token_of_slot, tp_rank, tp_size, share, (hipStream_t)stream);
+}
+
+moe_status_t moe_dtd_drop(const moe_shape_t *shape, const void *buf, const int32_t *kept, int32_t tp_rank,
+                          int32_t tp_size, void *share, void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if ((st = check_tp("moe_dtd_drop", shape, tp_rank, tp_size)) != MOE_OK) return st;
+    REQUIRE_PTR(buf);
+    REQUIRE_PTR(kept);
+    REQUIRE_PTR(share);
+    return run_dtd_drop(shape, buf, kept, tp_rank, tp_size, share, (hipStream_t)stream);
+}
+
+moe_status_t moe_dtd_gather(const moe_shape_t *shape, const void *shares, const int32_t *kept, int32_t tp_size,
+                            void *buf, void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if ((st = check_tp("moe_dtd_gather", shape, 0, tp_size)) != MOE_OK) return st;
+    REQUIRE_PTR(shares);
+    REQUIRE_PTR(kept);
+    REQUIRE_PTR(buf);
+    return run_dtd_gather(shape, shares, kept, tp_size, buf, (hipStream_t)stream);
+}
+
+moe_status_t moe_expert_ffn_fwd_dtd(const moe_shape_t *shape, const void *shares, int32_t tp_size, const void *w1,
+                                    const void *w2, const int32_t *kept, void *z_save, void *hact, void *y, void *ws,
+                                    size_t ws_bytes, void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if ((st = check_tp("moe_expert_ffn_fwd_dtd", shape, 0, tp_size)) != MOE_OK) return st;
+    if (shape->dtype != MOE_BF16) {
+        set_error("moe_expert_ffn_fwd_dtd: bf16 storage only (use moe_dtd_gather, then moe_expert_ffn_fwd)");
+        return MOE_ERR_UNSUPPORTED;
+    }
+    const int64_t Cg = (shape->C + tp_size - 1) / tp_size;
+    if ((double)tp_size * shape->E * (double)Cg * shape->h * 2.0 >= 2147483648.0) {
+        set_error("moe_expert_ffn_fwd_dtd: the shares span %.0f bytes, beyond the 2 GiB a gathered operand can span",
+                  (double)tp_size * shape->E * (double)Cg * shape->h * 2.0);
+        return MOE_ERR_UNSUPPORTED;
+    }
+    REQUIRE_PTR(shares);
+    REQUIRE_PTR(w1);
+    REQUIRE_PTR(w2);
+    REQUIRE_PTR(kept);
+    OPTIONAL_PTR(z_save);
+    OPTIONAL_PTR(hact);
+    REQUIRE_PTR(y);
+    const bool own_hact = hact == nullptr;
+    st = check_ws("moe_expert_ffn_fwd_dtd", ws, ws_bytes, ffn_fwd_ws_bytes(shape, own_hact));
+    if (st != MOE_OK) return st;
+    if (own_hact) hact = ws;
+    return ffn_fwd_launch(*shape, shares, w1, w2, kept, z_save, hact, y,
+                          (char *)ws + (own_hact ? dz_bytes(shape) : 0), (hipStream_t)stream, tp_size);
+}
+
+moe_status_t moe_dispatch_bwd_dtd(const moe_shape_t *shape, const void *d_shares, int32_t tp_size,
+                                  const int32_t *expert, const int32_t *slot, void *d_x, const float *d_logits,
+                                  const float *w_gate, void *stream) {
+    moe_status_t st = check_shape(shape);
+    if (st != MOE_OK) return st;
+    if ((st = check_tp("moe_dispatch_bwd_dtd", shape, 0, tp_size)) != MOE_OK) return st;
+    REQUIRE_PTR(d_shares);
+    REQUIRE_PTR(expert);
+    REQUIRE_PTR(slot);
+    REQUIRE_PTR(d_x);
+    OPTIONAL_PTR(d_logits);
+    OPTIONAL_PTR(w_gate);
+    if ((d_logits == nullptr) != (w_gate == nullptr)) {
+        set_error("moe_dispatch_bwd_dtd: d_logits and w_gate must be given together");
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (d_logits == nullptr) return run_dispatch_bwd(shape, d_shares, expert, slot, d_x, (hipStream_t)stream, tp_size);
+    if (shape->dtype == MOE_BF16)
+        return run_dispatch_bwd_fused(shape, d_shares, expert, slot, d_x, d_logits, w_gate, (hipStream_t)stream, tp_size);
+    st = run_dispatch_bwd(shape, d_shares, expert, slot, d_x, (hipStream_t)stream, tp_size);
+    if (st != MOE_OK) return st;
+    return run_gate_dx_f32(shape, d_logits, w_gate, d_x, (hipStream_t)stream);
 }
 
 moe_status_t moe_combine(const moe_shape_t *shape, const void *y, const int32_t *expert, const int32_t *slot,

@@ -64,8 +64,11 @@ struct GemmDesc {
     //   c_index != null (EPI_STORE): row r of expert e's result, times c_scale[e*M + r] and rounded again, is
     //   also written to row c_index[e*M + r] of C_scatter [*, ldc] (combine folded into the epilogue); C may
     //   then be null.
+    //   a_dtd_g = G > 1 (instead of a_index): A is the array of the G row shares of duplicate token dropping,
+    //   [G, E, a_dtd_cg, lda]: row r of expert e's operand is row r / G of share r % G (a_rows = G * E * a_dtd_cg).
     const int32_t *a_index;
     int64_t a_rows;
+    int32_t a_dtd_g, a_dtd_cg;
     const int32_t *c_index;
     const float *c_scale;
     void *C_scatter;

@@ -46,14 +46,56 @@ __global__ __launch_bounds__(256) void dispatch_kernel(const u32x4 *x, const int
     }
 }
 
-// dst[t,:] = src[expert[t], slot[t], :] or 0 (dispatch backward).
+// ---- duplicate token dropping: rank r of a tensor-parallel group of G keeps rows r, r + G, ... of every
+// expert chunk (row s of the chunk is row s / G of share s % G); shares are [E, Cg, words], Cg = ceil(C / G).
+
+// dispatch fused with the drop: share[e, j, :] = x[token_of_slot[e, j G + r], :] for filled slots
+__global__ __launch_bounds__(256) void dispatch_dtd_kernel(const u32x4 *x, const int32_t *token_of_slot, u32x4 *share,
+                                                            int64_t rows, int64_t C, int64_t Cg, int G, int r, int words) {
+    for (int64_t q = blockIdx.x; q < rows; q += gridDim.x) {
+        const int64_t e = q / Cg, s = (q - e * Cg) * G + r;
+        if (s >= C) continue;
+        const int tok = token_of_slot[e * C + s];
+        if (tok < 0) continue;
+        u32x4 *dst = share + q * words;
+        const u32x4 *src = x + (int64_t)tok * words;
+        for (int i = threadIdx.x; i < words; i += 256) dst[i] = src[i];
+    }
+}
+
+// the drop alone: share[e, j, :] = buf[e, j G + r, :] for j G + r < kept[e]
+__global__ __launch_bounds__(256) void dtd_drop_kernel(const u32x4 *buf, const int32_t *kept, u32x4 *share, int64_t rows,
+                                                        int64_t C, int64_t Cg, int G, int r, int words) {
+    for (int64_t q = blockIdx.x; q < rows; q += gridDim.x) {
+        const int64_t e = q / Cg, s = (q - e * Cg) * G + r;
+        if (s >= kept[e]) continue;
+        u32x4 *dst = share + q * words;
+        const u32x4 *src = buf + (e * C + s) * words;
+        for (int i = threadIdx.x; i < words; i += 256) dst[i] = src[i];
+    }
+}
+
+// the shares of all G ranks put back in row order: buf[e, s, :] = shares[s % G][e, s / G, :] for s < kept[e]
+__global__ __launch_bounds__(256) void dtd_gather_kernel(const u32x4 *shares, const int32_t *kept, u32x4 *buf,
+                                                          int64_t rows, int64_t C, int64_t Cg, int G, int E, int words) {
+    for (int64_t q = blockIdx.x; q < rows; q += gridDim.x) {
+        const int64_t e = q / C, s = q - e * C;
+        if (s >= kept[e]) continue;
+        u32x4 *dst = buf + q * words;
+        const u32x4 *src = shares + (((s % G) * E + e) * Cg + s / G) * words;
+        for (int i = threadIdx.x; i < words; i += 256) dst[i] = src[i];
+    }
+}
+
+// dst[t,:] = src[expert[t], slot[t], :] or 0 (dispatch backward).  G > 1: src holds the G shares
+// [G, E, Cg, words] of duplicate token dropping instead of whole chunks (G = 1, Cg = C: the plain layout).
 __global__ __launch_bounds__(256) void gather_rows_kernel(const u32x4 *src, const int32_t *expert, const int32_t *slot,
-                                                           u32x4 *dst, int64_t T, int64_t C, int words) {
+                                                           u32x4 *dst, int64_t T, int64_t Cg, int G, int E, int words) {
     for (int64_t t = blockIdx.x; t < T; t += gridDim.x) {
         const int s = slot[t];
         u32x4 *o = dst + t * words;
         if (s >= 0) {
-            const u32x4 *p = src + ((int64_t)expert[t] * C + s) * words;
+            const u32x4 *p = src + (((int64_t)(s % G) * E + expert[t]) * Cg + s / G) * words;
             for (int i = threadIdx.x; i < words; i += 256) o[i] = p[i];
         } else {
             const u32x4 z = {0u, 0u, 0u, 0u};
@@ -166,13 +208,43 @@ moe_status_t run_dispatch(const moe_shape_t *sh, const void *x, const int32_t *t
     return check_launch("dispatch");
 }
 
+// tp_size = 1: d_buf is [E, C, h]; tp_size = G > 1: d_buf holds the G shares [G, E, ceil(C/G), h]
 moe_status_t run_dispatch_bwd(const moe_shape_t *sh, const void *d_buf, const int32_t *expert, const int32_t *slot,
-                              void *d_x, hipStream_t s) {
+                              void *d_x, hipStream_t s, int tp_size) {
     const int esz = sh->dtype == MOE_BF16 ? 2 : 4;
     const int words = sh->h * esz / 16;
+    const int64_t Cg = (sh->C + tp_size - 1) / tp_size;
     hipLaunchKernelGGL(gather_rows_kernel, dim3(row_grid(sh->T)), dim3(256), 0, s, (const u32x4 *)d_buf, expert, slot,
-                       (u32x4 *)d_x, sh->T, sh->C, words);
+                       (u32x4 *)d_x, sh->T, Cg, tp_size, sh->E, words);
     return check_launch("dispatch_bwd");
+}
+
+moe_status_t run_dispatch_dtd(const moe_shape_t *sh, const void *x, const int32_t *token_of_slot, int tp_rank,
+                              int tp_size, void *share, hipStream_t s) {
+    const int words = sh->h * (sh->dtype == MOE_BF16 ? 2 : 4) / 16;
+    const int64_t Cg = (sh->C + tp_size - 1) / tp_size, rows = (int64_t)sh->E * Cg;
+    hipLaunchKernelGGL(dispatch_dtd_kernel, dim3(row_grid(rows)), dim3(256), 0, s, (const u32x4 *)x, token_of_slot,
+                       (u32x4 *)share, rows, sh->C, Cg, tp_size, tp_rank, words);
+    return check_launch("dispatch_dtd");
+}
+
+// width: elements per row (h for buf / d_buf)
+moe_status_t run_dtd_drop(const moe_shape_t *sh, const void *buf, const int32_t *kept, int tp_rank, int tp_size,
+                          void *share, hipStream_t s) {
+    const int words = sh->h * (sh->dtype == MOE_BF16 ? 2 : 4) / 16;
+    const int64_t Cg = (sh->C + tp_size - 1) / tp_size, rows = (int64_t)sh->E * Cg;
+    hipLaunchKernelGGL(dtd_drop_kernel, dim3(row_grid(rows)), dim3(256), 0, s, (const u32x4 *)buf, kept, (u32x4 *)share,
+                       rows, sh->C, Cg, tp_size, tp_rank, words);
+    return check_launch("dtd_drop");
+}
+
+moe_status_t run_dtd_gather(const moe_shape_t *sh, const void *shares, const int32_t *kept, int tp_size, void *buf,
+                            hipStream_t s) {
+    const int words = sh->h * (sh->dtype == MOE_BF16 ? 2 : 4) / 16;
+    const int64_t Cg = (sh->C + tp_size - 1) / tp_size, rows = (int64_t)sh->E * sh->C;
+    hipLaunchKernelGGL(dtd_gather_kernel, dim3(row_grid(rows)), dim3(256), 0, s, (const u32x4 *)shares, kept,
+                       (u32x4 *)buf, rows, sh->C, Cg, tp_size, sh->E, words);
+    return check_launch("dtd_gather");
 }
 
 moe_status_t run_combine(const moe_shape_t *sh, const void *y, const int32_t *expert, const int32_t *slot,

@@ -20,7 +20,8 @@ MOE_GELU_ERF, MOE_GELU_TANH = 0, 1
 EXPORTS = ["moe_capacity", "moe_workspace_bytes", "moe_status_string", "moe_last_error", "moe_version", "moe_gate",
            "moe_dispatch", "moe_expert_ffn_fwd", "moe_combine", "moe_combine_bwd", "moe_expert_ffn_bwd",
            "moe_dispatch_bwd", "moe_gate_bwd", "moe_adamw_tiled", "moe_expert_ffn_fwd_fused",
-           "moe_expert_ffn_fwd_static", "moe_launch_floor"]
+           "moe_expert_ffn_fwd_static", "moe_launch_floor", "moe_dispatch_dtd", "moe_dtd_drop", "moe_dtd_gather",
+           "moe_expert_ffn_fwd_dtd", "moe_dispatch_bwd_dtd"]
 MOE_STATIC_SCRATCH_BYTES = 256 * 1024
 
 
@@ -66,6 +67,11 @@ def lib():
             "moe_expert_ffn_fwd": [sp] + [vp] * 7 + [vp, sz, vp],
             "moe_expert_ffn_fwd_static": [sp] + [vp] * 7 + [vp],
             "moe_launch_floor": [i32, vp],
+            "moe_dispatch_dtd": [sp, vp, vp, i32, i32, vp, vp],
+            "moe_dtd_drop": [sp, vp, vp, i32, i32, vp, vp],
+            "moe_dtd_gather": [sp, vp, vp, i32, vp, vp],
+            "moe_expert_ffn_fwd_dtd": [sp, vp, i32] + [vp] * 6 + [vp, sz, vp],
+            "moe_dispatch_bwd_dtd": [sp, vp, i32] + [vp] * 5 + [vp],
             "moe_combine": [sp] + [vp] * 5 + [vp],
             "moe_expert_ffn_fwd_fused": [sp] + [vp] * 12 + [vp, sz, vp],
             "moe_combine_bwd": [sp] + [vp] * 7 + [vp],
@@ -157,6 +163,30 @@ def moe_expert_ffn_fwd_fused(shape, x, buf, token_of_slot, slot, gate_p, w1, w2,
     _check(lib().moe_expert_ffn_fwd_fused(C.byref(shape), _ptr(x), _ptr(buf), _ptr(token_of_slot), _ptr(slot),
                                           _ptr(gate_p), _ptr(w1), _ptr(w2), _ptr(kept), _ptr(z_save), _ptr(hact),
                                           _ptr(y), _ptr(out), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def moe_dispatch_dtd(shape, x, token_of_slot, tp_rank, tp_size, share, stream=None):
+    _check(lib().moe_dispatch_dtd(C.byref(shape), _ptr(x), _ptr(token_of_slot), int(tp_rank), int(tp_size), _ptr(share),
+                                  _stream(stream)))
+
+
+def moe_dtd_drop(shape, buf, kept, tp_rank, tp_size, share, stream=None):
+    _check(lib().moe_dtd_drop(C.byref(shape), _ptr(buf), _ptr(kept), int(tp_rank), int(tp_size), _ptr(share),
+                              _stream(stream)))
+
+
+def moe_dtd_gather(shape, shares, kept, tp_size, buf, stream=None):
+    _check(lib().moe_dtd_gather(C.byref(shape), _ptr(shares), _ptr(kept), int(tp_size), _ptr(buf), _stream(stream)))
+
+
+def moe_expert_ffn_fwd_dtd(shape, shares, tp_size, w1, w2, kept, z_save, hact, y, ws, stream=None):
+    _check(lib().moe_expert_ffn_fwd_dtd(C.byref(shape), _ptr(shares), int(tp_size), _ptr(w1), _ptr(w2), _ptr(kept),
+                                        _ptr(z_save), _ptr(hact), _ptr(y), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def moe_dispatch_bwd_dtd(shape, d_shares, tp_size, expert, slot, d_x, d_logits=None, w_gate=None, stream=None):
+    _check(lib().moe_dispatch_bwd_dtd(C.byref(shape), _ptr(d_shares), int(tp_size), _ptr(expert), _ptr(slot), _ptr(d_x),
+                                      _ptr(d_logits), _ptr(w_gate), _stream(stream)))
 
 
 def moe_combine(shape, y, expert, slot, gate_p, out, stream=None):

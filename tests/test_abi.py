@@ -160,6 +160,22 @@ def test_static_scratch_forward_arguments():
     assert b"static scratch" in L.moe_last_error() and str(moe.MOE_STATIC_SCRATCH_BYTES).encode() in L.moe_last_error()
 
 
+def test_duplicate_token_dropping_arguments():
+    sh = moe.make_shape(1024, 512, 8, 512, 128)
+    a = 4096
+    for rank, size in ((0, 0), (2, 2), (-1, 4), (0, 129)):
+        with pytest.raises(moe.MoeError) as ei:
+            moe.moe_dispatch_dtd(sh, a, a, rank, size, a, stream=0)
+        assert ei.value.status == moe.MOE_ERR_INVALID_ARG and "tp_size" in str(ei.value)
+    sh32 = moe.make_shape(1024, 512, 8, 512, 128, moe.MOE_F32)
+    with pytest.raises(moe.MoeError) as ei:
+        moe.lib()  # ws is passed as a raw pointer below
+        st = moe.lib().moe_expert_ffn_fwd_dtd(C.byref(sh32), C.c_void_p(a), 2, C.c_void_p(a), C.c_void_p(a), C.c_void_p(a), None,
+                                              C.c_void_p(a), C.c_void_p(a), C.c_void_p(a), 1 << 40, None)
+        raise moe.MoeError(st, moe.lib().moe_last_error().decode())
+    assert ei.value.status == moe.MOE_ERR_UNSUPPORTED
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(moe, "_lib", None)
     monkeypatch.setattr(moe, "LIB_PATH", "/nonexistent/libmoe_ted.so")
