@@ -6,10 +6,12 @@
 // result has fp32 dot-product accuracy while X is streamed once at HBM speed.
 // fp32 tokens: plain fp32 FMA dot products (small workloads only).
 //
-// Routing: two small kernels.  (1) per-1024-token block histograms (integer LDS atomics: the
-// result does not depend on their order); (2) every block adds the histograms of the blocks
-// before it, ranks its own tokens with wave ballots (token order inside a wave = lane order),
-// and writes slot / token_of_slot; the last block writes counts and kept.
+// Routing: per-token-block histograms of the chosen experts (integer LDS atomics: the result does not
+// depend on their order), written by the gate kernel itself for bf16 tokens (a block = the 64 or 16
+// tokens of a workgroup) and by a small kernel otherwise (blocks of 1024 tokens); then one kernel in
+// which every block of 1024 tokens adds up the histograms of the tokens before it (all threads in
+// parallel, integer atomics again), ranks its own tokens with wave ballots (token order inside a wave
+// = lane order) and writes slot / token_of_slot; the last block writes counts and kept.
 #include "moe_common.h"
 
 namespace moe {
@@ -32,25 +34,6 @@ __global__ void gate_split_wg_kernel(const float *wg, bf16_t *planes, int h, int
     planes[2 * n + i] = lo;
 }
 
-// ------------------------------------------------------------------ softmax + top-1 of one row held in LDS/global
-// row: E fp32 logits (already biased).  Returns expert and p; optionally writes probs.
-__device__ __forceinline__ void softmax_top1_row(const float *row, int rstride, int E, float *probs_out,
-                                                 int32_t *expert_out, float *p_out) {
-    float best = row[0];
-    int bi = 0;
-    for (int j = 1; j < E; ++j) {
-        float v = row[j * rstride];
-        if (v > best) { best = v; bi = j; }      // strict: the lowest index among equal maxima wins
-    }
-    float denom = 0.f;
-    for (int j = 0; j < E; ++j) denom += expf(row[j * rstride] - best);
-    float inv = 1.0f / denom;
-    *expert_out = bi;
-    *p_out = inv;
-    if (probs_out)
-        for (int j = 0; j < E; ++j) probs_out[j] = expf(row[j * rstride] - best) * inv;
-}
-
 // ------------------------------------------------------------------ fused gate, bf16 tokens
 // Workgroup: NW waves, 16*R tokens.  Wave w takes k-steps w, w+NW, ... (32 k each); the NW partial
 // [16R x Epad] tiles are summed through LDS in a fixed order.  The three planes of Wg are read from
@@ -58,10 +41,12 @@ __device__ __forceinline__ void softmax_top1_row(const float *row, int rstride, 
 template <int NT, int R, int NW, int U>
 __global__ __launch_bounds__(64 * NW) void gate_bf16_kernel(const bf16_t *x, const bf16_t *planes, const float *bias,
                                                          float *logits, float *probs, int32_t *expert,
-                                                         float *gate_p, int64_t T, int h, int E) {
+                                                         float *gate_p, int64_t T, int h, int E, int32_t *hist,
+                                                         int32_t *token_of_slot, int64_t EC) {
     constexpr int EP = NT * 16;
     constexpr int TM = 16 * R;
     __shared__ float part[NW][TM][EP + 1];
+    __shared__ int32_t hist_s[EP];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t t0 = (int64_t)blockIdx.x * TM;
     const int i16 = lane & 15, g = lane >> 4;
@@ -130,11 +115,47 @@ __global__ __launch_bounds__(64 * NW) void gate_bf16_kernel(const bf16_t *x, con
         part[0][tt][j] = v;
         if (t0 + tt < T) logits[(t0 + tt) * E + j] = v;
     }
+    if (tid < EP) hist_s[tid] = 0;
     __syncthreads();
-    if (tid < TM && t0 + tid < T) {
-        int64_t t = t0 + tid;
-        softmax_top1_row(&part[0][tid][0], 1, E, probs ? probs + t * E : nullptr, expert + t, gate_p + t);
+    // Softmax and top-1 with TPT adjacent lanes per token: lane `sub` looks at experts sub, sub + TPT, ...;
+    // the lanes' candidates are merged by butterfly exchanges (larger logit wins, the lower index among
+    // equal ones: the same choice as a left-to-right scan with a strict comparison).
+    constexpr int TPT = 64 * NW / TM;
+    static_assert(TPT >= 1 && (TPT & (TPT - 1)) == 0 && TPT <= 64, "lanes per token");
+    const int tt = tid / TPT, sub = tid % TPT;
+    const float *row = &part[0][tt][0];
+    float best = -__builtin_inff();
+    int bi = 0x7fffffff;
+    for (int j = sub; j < E; j += TPT) {
+        const float v = row[j];
+        if (v > best || bi == 0x7fffffff) { best = v; bi = j; }      // strict: the first of equal values stays
     }
+#pragma unroll
+    for (int o = 1; o < TPT; o <<= 1) {
+        const float ov = __shfl_xor(best, o);
+        const int oi = __shfl_xor(bi, o);
+        if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+    }
+    float denom = 0.f;
+    for (int j = sub; j < E; j += TPT) denom += expf(row[j] - best);
+#pragma unroll
+    for (int o = 1; o < TPT; o <<= 1) denom += __shfl_xor(denom, o);
+    const float inv = 1.0f / denom;
+    const int64_t t = t0 + tt;
+    if (t < T) {
+        if (probs)
+            for (int j = sub; j < E; j += TPT) probs[t * E + j] = expf(row[j] - best) * inv;
+        if (sub == 0) {
+            expert[t] = bi;
+            gate_p[t] = inv;
+            atomicAdd(&hist_s[bi], 1);
+        }
+    }
+    __syncthreads();
+    // the routing kernel's inputs: this block's histogram, and its share of the inverse map cleared
+    if (tid < E) hist[(int64_t)blockIdx.x * E + tid] = hist_s[tid];
+    const int64_t per = (EC + gridDim.x - 1) / gridDim.x, i0 = (int64_t)blockIdx.x * per;
+    for (int64_t i = i0 + tid; i < i0 + per && i < EC; i += 64 * NW) token_of_slot[i] = -1;
 }
 
 // ------------------------------------------------------------------ fp32 tokens: logits by fp32 FMA, one wave per token
@@ -162,12 +183,38 @@ __global__ __launch_bounds__(256) void gate_logits_f32_kernel(const float *x, co
     }
 }
 
-// softmax + top-1 from stored logits, one thread per token
-__global__ void gate_softmax_top1_kernel(const float *logits, float *probs, int32_t *expert, float *gate_p,
-                                         int64_t T, int E) {
-    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+// softmax + top-1 from stored logits: 16 adjacent lanes per token, lane `sub` looks at experts sub, sub + 16, ...
+// (consecutive lanes read consecutive logits); candidates merged by butterfly exchanges, lower index among equals
+constexpr int SM_TPT = 16;
+__global__ __launch_bounds__(256) void gate_softmax_top1_kernel(const float *logits, float *probs, int32_t *expert,
+                                                                 float *gate_p, int64_t T, int E) {
+    const int64_t t = ((int64_t)blockIdx.x * 256 + threadIdx.x) / SM_TPT;
+    const int sub = threadIdx.x % SM_TPT;
+    const float *row = logits + (t < T ? t : 0) * E;         // lanes past the end work on row 0 and write nothing
+    float best = -__builtin_inff();
+    int bi = 0x7fffffff;
+    for (int j = sub; j < E; j += SM_TPT) {
+        const float v = row[j];
+        if (v > best || bi == 0x7fffffff) { best = v; bi = j; }
+    }
+#pragma unroll
+    for (int o = 1; o < SM_TPT; o <<= 1) {
+        const float ov = __shfl_xor(best, o);
+        const int oi = __shfl_xor(bi, o);
+        if (ov > best || (ov == best && oi < bi)) { best = ov; bi = oi; }
+    }
+    float denom = 0.f;
+    for (int j = sub; j < E; j += SM_TPT) denom += expf(row[j] - best);
+#pragma unroll
+    for (int o = 1; o < SM_TPT; o <<= 1) denom += __shfl_xor(denom, o);
+    const float inv = 1.0f / denom;
     if (t >= T) return;
-    softmax_top1_row(logits + t * E, 1, E, probs ? probs + t * E : nullptr, expert + t, gate_p + t);
+    if (probs)
+        for (int j = sub; j < E; j += SM_TPT) probs[t * E + j] = expf(row[j] - best) * inv;
+    if (sub == 0) {
+        expert[t] = bi;
+        gate_p[t] = inv;
+    }
 }
 
 // ------------------------------------------------------------------ routing
@@ -186,18 +233,23 @@ __global__ __launch_bounds__(RB) void route_hist_kernel(const int32_t *expert, i
     for (int64_t i = (int64_t)blockIdx.x * RB + tid; i < EC; i += (int64_t)gridDim.x * RB) token_of_slot[i] = -1;
 }
 
+// hist holds one row of E counts per `hist_block` tokens (RB is a multiple of hist_block).
 __global__ __launch_bounds__(RB) void route_slot_kernel(const int32_t *expert, const int32_t *hist, int32_t *slot,
                                                          int32_t *counts, int32_t *kept, int32_t *token_of_slot,
-                                                         int64_t T, int E, int64_t C) {
+                                                         int64_t T, int E, int64_t C, int hist_block) {
     __shared__ int32_t base[256];
     __shared__ int32_t wcnt[RB / 64][256];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = blockIdx.x;
     for (int i = tid; i < (RB / 64) * 256; i += RB) (&wcnt[0][0])[i] = 0;
-    if (tid < E) {
-        int32_t s = 0;
-        for (int bb = 0; bb < b; ++bb) s += hist[(int64_t)bb * E + tid];
-        base[tid] = s;
+    if (tid < 256) base[tid] = 0;
+    __syncthreads();
+    // tokens before this block: all histogram rows in front of it, summed by all threads at once
+    // (consecutive threads read consecutive counts; integer atomics, so the order does not matter)
+    const int64_t n_before = (int64_t)b * (RB / hist_block) * E;
+    for (int64_t i = tid; i < n_before; i += RB) {
+        const int32_t v = hist[i];
+        if (v) atomicAdd(&base[(int)(i % E)], v);
     }
     __syncthreads();
     const int64_t t = (int64_t)b * RB + tid;
@@ -244,17 +296,18 @@ size_t gate_ws_bytes(const moe_shape_t *sh) {
     int NT = 1;
     while (NT * 16 < sh->E) NT *= 2;
     size_t planes = (size_t)3 * NT * 16 * sh->h * 2;
-    size_t hist = (size_t)((sh->T + RB - 1) / RB) * sh->E * 4;
+    size_t hist = (size_t)((sh->T + 15) / 16) * sh->E * 4;        // one row per 16 tokens at most (see run_gate)
     return ((planes + 255) / 256) * 256 + ((hist + 255) / 256) * 256;
 }
 
 template <int NT, int R, int NW, int U>
 static void launch_gate_bf16(const moe_shape_t *sh, const void *x, const bf16_t *planes, const float *bias,
-                             float *logits, float *probs, int32_t *expert, float *gate_p, hipStream_t s) {
+                             float *logits, float *probs, int32_t *expert, float *gate_p, int32_t *hist,
+                             int32_t *token_of_slot, hipStream_t s) {
     const int TM = 16 * R;
     dim3 grid((unsigned)((sh->T + TM - 1) / TM));
     hipLaunchKernelGGL((gate_bf16_kernel<NT, R, NW, U>), grid, dim3(64 * NW), 0, s, (const bf16_t *)x, planes, bias, logits,
-                       probs, expert, gate_p, sh->T, sh->h, sh->E);
+                       probs, expert, gate_p, sh->T, sh->h, sh->E, hist, token_of_slot, (int64_t)sh->E * sh->C);
 }
 
 moe_status_t run_gate(const moe_shape_t *sh, const void *x, const float *w_gate, const float *bias, float *logits,
@@ -267,12 +320,12 @@ moe_status_t run_gate(const moe_shape_t *sh, const void *x, const float *w_gate,
     int32_t *hist = (int32_t *)((char *)ws + planes_bytes);
     const int64_t T = sh->T;
     if (x == nullptr) {
-        hipLaunchKernelGGL(gate_softmax_top1_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, s, logits,
+        hipLaunchKernelGGL(gate_softmax_top1_kernel, dim3((unsigned)((T * SM_TPT + 255) / 256)), dim3(256), 0, s, logits,
                            probs, expert, gate_p, T, sh->E);
     } else if (sh->dtype == MOE_F32) {
         hipLaunchKernelGGL(gate_logits_f32_kernel, dim3((unsigned)((T + 3) / 4)), dim3(256), 0, s, (const float *)x,
                            w_gate, bias, logits, T, sh->h, sh->E);
-        hipLaunchKernelGGL(gate_softmax_top1_kernel, dim3((unsigned)((T + 255) / 256)), dim3(256), 0, s, logits,
+        hipLaunchKernelGGL(gate_softmax_top1_kernel, dim3((unsigned)((T * SM_TPT + 255) / 256)), dim3(256), 0, s, logits,
                            probs, expert, gate_p, T, sh->E);
     } else {
         const int64_t n = (int64_t)NT * 16 * sh->h;
@@ -280,20 +333,25 @@ moe_status_t run_gate(const moe_shape_t *sh, const void *x, const float *w_gate,
                            sh->h, sh->E, NT * 16);
         // template arguments: 16-expert tiles, tokens per workgroup / 16, waves, k-steps in flight per wave
         switch (NT) {
-            case 1: launch_gate_bf16<1, 4, 8, 4>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
-            case 2: launch_gate_bf16<2, 4, 8, 2>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
-            case 4: launch_gate_bf16<4, 4, 8, 2>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
-            case 8: launch_gate_bf16<8, 1, 4, 4>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
-            default: launch_gate_bf16<16, 1, 4, 4>(sh, x, planes, bias, logits, probs, expert, gate_p, s); break;
+            case 1: launch_gate_bf16<1, 4, 8, 4>(sh, x, planes, bias, logits, probs, expert, gate_p, hist, token_of_slot, s); break;
+            case 2: launch_gate_bf16<2, 4, 8, 2>(sh, x, planes, bias, logits, probs, expert, gate_p, hist, token_of_slot, s); break;
+            case 4: launch_gate_bf16<4, 4, 8, 2>(sh, x, planes, bias, logits, probs, expert, gate_p, hist, token_of_slot, s); break;
+            case 8: launch_gate_bf16<8, 1, 4, 4>(sh, x, planes, bias, logits, probs, expert, gate_p, hist, token_of_slot, s); break;
+            default: launch_gate_bf16<16, 1, 4, 4>(sh, x, planes, bias, logits, probs, expert, gate_p, hist, token_of_slot, s); break;
         }
     }
     moe_status_t st = check_launch("gate");
     if (st != MOE_OK) return st;
     const unsigned nb = (unsigned)((T + RB - 1) / RB);
-    hipLaunchKernelGGL(route_hist_kernel, dim3(nb), dim3(RB), 0, s, expert, hist, token_of_slot, T, sh->E,
-                       (int64_t)sh->E * sh->C);
+    int hist_block = RB;
+    if (x != nullptr && sh->dtype == MOE_BF16) {
+        hist_block = NT >= 8 ? 16 : 64;          // the gate kernel has written a histogram per workgroup (16 R tokens)
+    } else {
+        hipLaunchKernelGGL(route_hist_kernel, dim3(nb), dim3(RB), 0, s, expert, hist, token_of_slot, T, sh->E,
+                           (int64_t)sh->E * sh->C);
+    }
     hipLaunchKernelGGL(route_slot_kernel, dim3(nb), dim3(RB), 0, s, expert, hist, slot, counts, kept, token_of_slot,
-                       T, sh->E, sh->C);
+                       T, sh->E, sh->C, hist_block);
     return check_launch("route");
 }
 
