@@ -122,6 +122,8 @@ def main() -> int:
                     help="dispatch folded into GEMM1's operand load (forward-only workloads) and combine into GEMM2's "
                          "epilogue (moe_expert_ffn_fwd_fused)")
     ap.add_argument("--tile-size", type=int, default=1_800_000, help="ts of the tiled optimizer step")
+    ap.add_argument("--no-isolated", action="store_true",
+                    help="skip the isolated timings of the HBM-bound phases (clean and dirty caches)")
     ap.add_argument("--dtd", type=int, default=0, metavar="G",
                     help="also time the local halves of duplicate token dropping for a tensor-parallel group of G "
                          "(reported in an extra \"dtd\" object; never part of ms_per_step)")
@@ -312,6 +314,45 @@ def main() -> int:
                                   f"({'fwd+bwd' if wl.backward else 'fwd'}, all {wl.E} experts, capacity {Cs}), "
                                   f"{tc1 - tc0:.1f} s"}
 
+    # The HBM-bound phases once more, each alone: after 1 GiB has been READ (the caches hold clean lines) and after
+    # 1 GiB has been WRITTEN (they hold dirty lines, as they do inside a training step, where every phase follows
+    # kernels that have just written hundreds of MB: each line a phase brings in then pushes a dirty line out, and
+    # that write-back shares the HBM with the phase's own traffic).  Medians, one event pair per call (includes
+    # about 6 us of launch and event overhead).
+    isolated = None
+    if not args.no_isolated:
+        big = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+        big.zero_()
+
+        def alone_us(fn, flush, n=7):
+            ts = []
+            for _ in range(n):
+                big.sum() if flush == "read" else big.fill_(1.0)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                fn()
+                e1.record()
+                torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1) * 1e3)
+            return sorted(ts)[n // 2]
+        calls = {
+            "gate": lambda: moe.moe_gate(sh, x, wg, bias, layer.logits, layer.probs, layer.expert, layer.gate_p, layer.slot,
+                                         layer.counts, layer.kept, layer.token_of_slot, layer.ws),
+            "dispatch": lambda: moe.moe_dispatch(sh, x, layer.token_of_slot, layer.buf),
+            "combine": lambda: moe.moe_combine(sh, layer.y, layer.expert, layer.slot, layer.gate_p, layer.out),
+        }
+        if wl.backward:
+            calls["combine_bwd"] = lambda: moe.moe_combine_bwd(sh, d_out, layer.y, layer.token_of_slot, layer.slot,
+                                                               layer.gate_p, layer.d_y, layer.d_gate_p)
+            calls["gate_bwd"] = lambda: moe.moe_gate_bwd(sh, layer.d_gate_p, layer.probs, layer.expert, x, wg,
+                                                         layer.d_logits, layer.d_w_gate, None, layer.ws)
+            calls["dispatch_bwd"] = lambda: moe.moe_dispatch_bwd(sh, layer.d_buf, layer.expert, layer.slot, layer.d_x,
+                                                                 layer.d_logits, wg)
+        isolated = {"unit": "us", "launch_and_event_overhead": round(alone_us(lambda: moe.moe_launch_floor(1), "read"), 1),
+                    "after_1GiB_read": {p: round(alone_us(f, "read"), 1) for p, f in calls.items()},
+                    "after_1GiB_write": {p: round(alone_us(f, "write"), 1) for p, f in calls.items()}}
+        del big
+
     dtd = None
     if args.dtd > 1:
         # One rank's drop fused with dispatch (1/G of the rows), the expert FFN reading all G shares in place, the
@@ -374,6 +415,8 @@ def main() -> int:
                           "against the same number of empty kernels, back to back on one stream"},
         "hbm_frac_of_8TBs": hbm_frac,
     }
+    if isolated is not None:
+        out["hbm_phases_alone"] = isolated
     if optimizer is not None:
         out["optimizer"] = optimizer
     if dtd is not None:

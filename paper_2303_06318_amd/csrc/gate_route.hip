@@ -67,35 +67,73 @@ __global__ __launch_bounds__(64 * NW) void gate_bf16_kernel(const bf16_t *x, con
     const __amdgpu_buffer_rsrc_t pr =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(planes), 0, (int)(3 * plane * 2), 0x00020000);
     const int nsteps = (h + 31) / 32;
-    for (int s = wave; s < nsteps; s += NW * U) {
-        bf16x8 a[U][R];
-        uint32_t koff[U];
+    // A batch = U k-steps of this wave: all its requests (R token fragments and 3 NT plane fragments per
+    // k-step) are issued together, and the arithmetic of a batch runs while the requests of the next one
+    // are in flight: two register sets alternate.  The scheduling barriers keep the compiler from
+    // trickling the loads out between the MFMAs (which it does to save registers, leaving a few KB in
+    // flight per wave: the kernel is bound by memory latency).  Batches past the end read zeros.
+    auto issue = [&](int s, bf16x8(&a)[U][R], bf16x8(&b)[U][NT][3]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int k = (s + NW * u) * 32 + g * 8;
-            koff[u] = k < h ? (uint32_t)k * 2u : OOB;
+            const uint32_t koff = k < h ? (uint32_t)k * 2u : OOB;
 #pragma unroll
             for (int r = 0; r < R; ++r)
                 a[u][r] = __builtin_bit_cast(
-                    bf16x8, __builtin_amdgcn_raw_buffer_load_b128(xr, (uint32_t)(r * 16 + i16) * h * 2u + koff[u], 0, 0));
-        }
+                    bf16x8, __builtin_amdgcn_raw_buffer_load_b128(xr, (uint32_t)(r * 16 + i16) * h * 2u + koff, 0, 0));
 #pragma unroll
-        for (int n = 0; n < NT; ++n) {
-            bf16x8 b[U][3];
-#pragma unroll
-            for (int u = 0; u < U; ++u)
+            for (int n = 0; n < NT; ++n)
 #pragma unroll
                 for (int p = 0; p < 3; ++p)
-                    b[u][p] = __builtin_bit_cast(
+                    b[u][n][p] = __builtin_bit_cast(
                         bf16x8, __builtin_amdgcn_raw_buffer_load_b128(
-                                    pr, (uint32_t)(p * plane + (int64_t)(n * 16 + i16) * h) * 2u + koff[u], 0, 0));
+                                    pr, (uint32_t)(p * plane + (int64_t)(n * 16 + i16) * h) * 2u + koff, 0, 0));
+        }
+    };
+    auto multiply = [&](const bf16x8(&a)[U][R], const bf16x8(&b)[U][NT][3]) {
 #pragma unroll
-            for (int u = 0; u < U; ++u)
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int n = 0; n < NT; ++n)
 #pragma unroll
                 for (int p = 0; p < 3; ++p)
 #pragma unroll
                     for (int r = 0; r < R; ++r)
-                        acc[r][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][r], b[u][p], acc[r][n], 0, 0, 0);
+                        acc[r][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][r], b[u][n][p], acc[r][n], 0, 0, 0);
+    };
+    // All workgroups read the same Wg planes.  Walking k in the same order, the workgroups of an XCD would ask
+    // its L2 for the same few lines at the same time (one or two of its 16 channels serving everybody), so each
+    // workgroup starts at a different batch and wraps around.
+    constexpr int BS = NW * U;                                   // k-steps per batch of the workgroup
+    const int nbatch = (nsteps + BS - 1) / BS;
+    const int nbatch2 = (nbatch + 1) & ~1;                       // the loop body holds two batches
+    const int rot = (int)((blockIdx.x >> 3) % (unsigned)nbatch2);        // blockIdx / 8: index inside the XCD
+    auto first_step = [&](int i) {                               // batch i of this workgroup, rotated; past the end: zeros
+        int bi = i + rot;
+        bi = bi >= nbatch2 ? bi - nbatch2 : bi;
+        return i < nbatch2 ? bi * BS + wave : nsteps;
+    };
+    constexpr bool TWO_SETS = 2 * U * (R + 3 * NT) * 4 <= 200;   // registers of two batches of fragments
+    if constexpr (TWO_SETS) {
+        bf16x8 aA[U][R], bA[U][NT][3], aB[U][R], bB[U][NT][3];
+        issue(first_step(0), aA, bA);
+        for (int i = 0; i < nbatch2; i += 2) {
+            issue(first_step(i + 1), aB, bB);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(aA, bA);
+            __builtin_amdgcn_sched_barrier(0);
+            issue(first_step(i + 2), aA, bA);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(aB, bB);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else {                                                     // many experts: one batch at a time
+        bf16x8 aA[U][R], bA[U][NT][3];
+        for (int i = 0; i < nbatch2; ++i) {
+            issue(first_step(i), aA, bA);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(aA, bA);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
     // 16x16 result: lane holds column (expert) lane%16, rows (tokens) 4*(lane/16) + v
@@ -331,13 +369,14 @@ moe_status_t run_gate(const moe_shape_t *sh, const void *x, const float *w_gate,
         const int64_t n = (int64_t)NT * 16 * sh->h;
         hipLaunchKernelGGL(gate_split_wg_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, w_gate, planes,
                            sh->h, sh->E, NT * 16);
-        // template arguments: 16-expert tiles, tokens per workgroup / 16, waves, k-steps in flight per wave
+        // template arguments: 16-expert tiles, tokens per workgroup / 16, waves, k-steps per batch (two batches in
+        // flight per wave: 2 U (R + 3 NT) fragments of 4 registers)
         switch (NT) {
-            case 1: launch_gate_bf16<1, 4, 8, 4>(sh, x, planes, bias, logits, probs, expert, gate_p, hist, token_of_slot, s); break;
+            case 1: launch_gate_bf16<1, 4, 8, 2>(sh, x, planes, bias, logits, probs, expert, gate_p, hist, token_of_slot, s); break;
             case 2: launch_gate_bf16<2, 4, 8, 2>(sh, x, planes, bias, logits, probs, expert, gate_p, hist, token_of_slot, s); break;
-            case 4: launch_gate_bf16<4, 4, 8, 2>(sh, x, planes, bias, logits, probs, expert, gate_p, hist, token_of_slot, s); break;
-            case 8: launch_gate_bf16<8, 1, 4, 4>(sh, x, planes, bias, logits, probs, expert, gate_p, hist, token_of_slot, s); break;
-            default: launch_gate_bf16<16, 1, 4, 4>(sh, x, planes, bias, logits, probs, expert, gate_p, hist, token_of_slot, s); break;
+            case 4: launch_gate_bf16<4, 4, 8, 1>(sh, x, planes, bias, logits, probs, expert, gate_p, hist, token_of_slot, s); break;
+            case 8: launch_gate_bf16<8, 1, 4, 1>(sh, x, planes, bias, logits, probs, expert, gate_p, hist, token_of_slot, s); break;
+            default: launch_gate_bf16<16, 1, 4, 1>(sh, x, planes, bias, logits, probs, expert, gate_p, hist, token_of_slot, s); break;
         }
     }
     moe_status_t st = check_launch("gate");
