@@ -29,12 +29,13 @@
  *    of device data (kept_e is read on the device, so launches cover C rows per
  *    expert and skip the unused part).  One exception to "only on `stream`":
  *    moe_expert_ffn_bwd (bf16) runs its two weight-gradient GEMMs on an internal
- *    stream, created once per device on first use and kept until the process ends;
- *    that stream starts behind an event of `stream` and `stream` waits for its last
+ *    stream that starts behind an event of `stream`, and `stream` waits for that stream's last
  *    event before the call's work is complete, so the caller still orders everything
- *    on `stream` alone.  That stream and its events are shared by all calls on a device:
- *    calling moe_expert_ffn_bwd from several host threads at once on one device is not
- *    supported (set MOE_TED_SERIAL=1 before the first call to keep everything on `stream`).
+ *    on `stream` alone.  One internal stream (and three events) exists per caller stream and device,
+ *    created on first use and kept until the process ends; calls on different streams do not share
+ *    one.  Two host threads must not call moe_expert_ffn_bwd on the SAME stream at once (they would
+ *    interleave on it anyway).  Beyond 8 caller streams per device, and always when MOE_TED_SERIAL=1
+ *    is set before the first call, everything stays on `stream`.
  *  - `dtype` is the storage type of x, buffers, expert weights and their
  *    gradients: MOE_BF16 (fp32 accumulation on MFMA) or MOE_F32.  The gate
  *    (w_gate, logits, probs, gate_p and their gradients) is always fp32.

@@ -190,34 +190,41 @@ static size_t ws_bytes_checked(const moe_shape_t *sh, int for_backward) {
 
 // Side stream of the FFN backward (bf16): the two weight-gradient GEMMs do not depend on the data-gradient
 // GEMM that runs next to them, and every GEMM launch ends with compute units idling while the last tiles
-// finish; on a second stream the other GEMM's workgroups move into those units as they free up.  One
-// stream and three events per device, created on first use and kept until the process ends; the side
+// finish; on a second stream the other GEMM's workgroups move into those units as they free up.  The side
 // stream starts behind an event of the caller's stream and the caller's stream waits for its last event,
 // so for the caller the call is still ordered on `stream` alone.
 struct SideStream {
-    hipStream_t stream = nullptr;
+    hipStream_t caller = nullptr, stream = nullptr;
     hipEvent_t fork = nullptr, mid = nullptr, join = nullptr;
-    bool ok = false, tried = false;
+    bool ok = false;
 };
-static SideStream *side_stream() {
-    static SideStream per_device[16];
+// One side stream (with its three events) per caller stream and device, created on first use and kept until the
+// process ends: layers that run on different streams do not share one, so their weight gradients are not
+// serialised against each other.  At most SIDE_SLOTS caller streams per device get one; a call on any further
+// stream, and every call when MOE_TED_SERIAL=1, keeps all its GEMMs on the caller's stream.
+constexpr int SIDE_SLOTS = 8;
+static SideStream *side_stream(hipStream_t caller) {
+    static SideStream slots[16][SIDE_SLOTS];
+    static int used[16] = {};
     static std::mutex mu;
+    static const bool serial = [] {
+        const char *e = getenv("MOE_TED_SERIAL");
+        return e != nullptr && e[0] == '1';
+    }();
+    if (serial) return nullptr;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
     std::lock_guard<std::mutex> lock(mu);
-    SideStream &ss = per_device[dev];
-    if (!ss.tried) {
-        ss.tried = true;
-        // MOE_TED_SERIAL=1 keeps everything on the caller's stream (per-kernel durations in a profile then
-        // are those of kernels that had the chip to themselves)
-        const char *serial = getenv("MOE_TED_SERIAL");
-        if (serial != nullptr && serial[0] == '1') return nullptr;
-        ss.ok = hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) == hipSuccess &&
-                hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming) == hipSuccess &&
-                hipEventCreateWithFlags(&ss.mid, hipEventDisableTiming) == hipSuccess &&
-                hipEventCreateWithFlags(&ss.join, hipEventDisableTiming) == hipSuccess;
-        if (!ss.ok) (void)hipGetLastError();
-    }
+    for (int i = 0; i < used[dev]; ++i)
+        if (slots[dev][i].caller == caller) return slots[dev][i].ok ? &slots[dev][i] : nullptr;
+    if (used[dev] == SIDE_SLOTS) return nullptr;
+    SideStream &ss = slots[dev][used[dev]++];
+    ss.caller = caller;
+    ss.ok = hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) == hipSuccess &&
+            hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming) == hipSuccess &&
+            hipEventCreateWithFlags(&ss.mid, hipEventDisableTiming) == hipSuccess &&
+            hipEventCreateWithFlags(&ss.join, hipEventDisableTiming) == hipSuccess;
+    if (!ss.ok) (void)hipGetLastError();
     return ss.ok ? &ss : nullptr;
 }
 
@@ -648,7 +655,7 @@ moe_status_t moe_expert_ffn_bwd(const moe_shape_t *shape, const void *d_y, const
         for (int i = 0; i < 4; ++i) { g[i].plan = pl; pl += gemm_bf16_plan_bytes(g[i]); }
         if ((st = launch_gemm_bf16_plans(g, 4, hs)) != MOE_OK) return st;
     }
-    SideStream *ss = bf ? side_stream() : nullptr;
+    SideStream *ss = bf ? side_stream(hs) : nullptr;
     if (ss == nullptr) {     // fp32, or no side stream: one after the other
         for (int i = 0; i < 4; ++i)
             if ((st = bf ? launch_gemm_bf16(g[i], hs) : launch_gemm_f32(g[i], hs)) != MOE_OK) return st;
