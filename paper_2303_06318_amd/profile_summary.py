@@ -3,7 +3,7 @@
 A session is a directory (kept under gpurun_out/, never committed) with these sub-directories, each written by
 one rocprofv3 run of the committed bench.py (the commands are repeated at the top of the summary this writes):
 
-    kt/     --kernel-trace --stats                       kt_kernel_stats.csv, bench.log
+    kt/     --kernel-trace --stats                       kt_kernel_stats.csv, bench.log   (the only one required)
     fetch/  --pmc FETCH_SIZE   (bench.py --copy-calibration)   f_counter_collection.csv
     write/  --pmc WRITE_SIZE   (bench.py --copy-calibration)   w_counter_collection.csv
     mfma/   --pmc MfmaUtil SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE   m_counter_collection.csv   (optional)
@@ -75,20 +75,27 @@ def main() -> int:
     ap.add_argument("--workload", required=True)
     ap.add_argument("--commit", required=True, help="the commit the profiled tree was built from")
     ap.add_argument("--out", default=None, help="summary file name under profiles/ (default: layer_<workload>.md)")
+    ap.add_argument("--bench-args", default="", help="further bench.py arguments the session's runs were made with (e.g. --fused)")
     args = ap.parse_args()
     S = args.session
+    wl_args = args.workload + (" " + args.bench_args.strip() if args.bench_args.strip() else "")
     out_md = os.path.join(ROOT, "profiles", args.out or "layer_%s.md" % args.workload)
     L = []
-    L.append("# rocprofv3 summaries: whole layer step, workload %s\n" % args.workload)
+    L.append("# rocprofv3 summaries: whole layer step, workload %s\n" % wl_args)
     L.append("Measured at commit %s; every section comes from one run of the committed bench.py, all runs in one session on one box." % args.commit)
     L.append("Commands (from /tmp with TMPDIR=/tmp; R = repository root, S = the session's output directory under gpurun_out/):\n")
     L.append("    export MOE_TED_SERIAL=1   # kernel trace only: every GEMM on the caller's stream, so durations are those of kernels that have the chip to themselves")
-    L.append("    rocprofv3 --kernel-trace --stats -d $S/kt -o kt --output-format csv -- python3 $R/bench.py --workload %s --steps 10 --warmup 3 --no-cpu-baseline --no-isolated" % args.workload)
+    L.append("    rocprofv3 --kernel-trace --stats -d $S/kt -o kt --output-format csv -- python3 $R/bench.py --workload %s --steps 10 --warmup 3 --no-cpu-baseline --no-isolated" % wl_args)
     L.append("    unset MOE_TED_SERIAL")
-    L.append("    rocprofv3 --pmc FETCH_SIZE -d $S/fetch -o f --output-format csv -- python3 $R/bench.py --workload %s --steps 2 --warmup 1 --no-cpu-baseline --no-isolated --copy-calibration" % args.workload)
-    L.append("    rocprofv3 --pmc WRITE_SIZE -d $S/write -o w --output-format csv -- python3 $R/bench.py --workload %s --steps 2 --warmup 1 --no-cpu-baseline --no-isolated --copy-calibration" % args.workload)
-    L.append("    rocprofv3 --pmc MfmaUtil SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE -d $S/mfma -o m --output-format csv -- python3 $R/bench.py --workload %s --steps 2 --warmup 1 --no-cpu-baseline --no-isolated" % args.workload)
-    L.append("    python3 -m paper_2303_06318_amd.profile_summary $S --workload %s --commit %s\n" % (args.workload, args.commit))
+    if os.path.isdir(os.path.join(S, "fetch")):
+        L.append("    rocprofv3 --pmc FETCH_SIZE -d $S/fetch -o f --output-format csv -- python3 $R/bench.py --workload %s --steps 2 --warmup 1 --no-cpu-baseline --no-isolated --copy-calibration" % wl_args)
+    if os.path.isdir(os.path.join(S, "write")):
+        L.append("    rocprofv3 --pmc WRITE_SIZE -d $S/write -o w --output-format csv -- python3 $R/bench.py --workload %s --steps 2 --warmup 1 --no-cpu-baseline --no-isolated --copy-calibration" % wl_args)
+    if os.path.isdir(os.path.join(S, "mfma")):
+        L.append("    rocprofv3 --pmc MfmaUtil SQ_LDS_BANK_CONFLICT SQ_LDS_IDX_ACTIVE -d $S/mfma -o m --output-format csv -- python3 $R/bench.py --workload %s --steps 2 --warmup 1 --no-cpu-baseline --no-isolated" % wl_args)
+    L.append("    python3 -m paper_2303_06318_amd.profile_summary $S --workload %s --commit %s%s%s\n" % (
+        args.workload, args.commit, " --bench-args='%s'" % args.bench_args.strip() if args.bench_args.strip() else "",
+        " --out %s" % args.out if args.out else ""))
 
     # ---- 1. kernel trace
     stats = kernel_stats(os.path.join(S, "kt", "kt_kernel_stats.csv"))
