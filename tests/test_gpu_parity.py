@@ -33,6 +33,9 @@ CASES = {
     "bf16_E256_C1": synth.scaled(W["cfg5_6p7b_tp4_fwdbwd"], T=300, h=72, f=40, E=256, capacity_factor=0.8),
     # 560 rows = 18 blocks = two 9-block tiles; 600 rows = 19 blocks = 7 + 6 + 6
     "bf16_bwd_18blocks": synth.scaled(W["cfg5_6p7b_tp4_fwdbwd"], T=1120, h=136, f=264, E=2, capacity_factor=1.0),
+    # every expert overflows and keeps exactly C = 768 rows = three full 256-row tiles: equal work everywhere,
+    # so every split point of the tile plan falls on an expert boundary
+    "bf16_bwd_all_full": synth.scaled(W["cfg5_6p7b_tp4_fwdbwd"], T=4096, h=264, f=520, E=4, capacity_factor=0.75),
 }
 
 
@@ -98,7 +101,7 @@ def test_forward_parity(orc, name):
 
 
 @pytest.mark.parametrize("name", ["cfg5_small", "f32_bwd", "bf16_one_expert", "bf16_bwd_E64", "bf16_bwd_E200",
-                                  "bf16_E256_C1", "bf16_bwd_9blocks", "bf16_bwd_18blocks"])
+                                  "bf16_E256_C1", "bf16_bwd_9blocks", "bf16_bwd_18blocks", "bf16_bwd_all_full"])
 @pytest.mark.parametrize("act", [moe.MOE_GELU_ERF, moe.MOE_GELU_TANH])
 def test_backward_parity(orc, name, act):
     wl = CASES[name]
