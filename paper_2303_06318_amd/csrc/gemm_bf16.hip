@@ -305,11 +305,18 @@ __global__ __launch_bounds__(PLAN_THREADS) void gemm_plan_kernel(PlanArgs args) 
         }
         // A share is worked off by the cus_per_xcd compute units of one XCD, a tile at a time: a few
         // tiles beyond a multiple of that number cost a whole extra round, so the split points are
-        // moved to the nearest multiple (this matters when there are only a few rounds).
+        // moved to the nearest multiple (this matters when there are only a few rounds).  With no more
+        // tiles than compute units there is one round if no share holds more tiles than its XCD has
+        // units: the shares are then equal in tile count, which also uses the memory paths of all XCDs
+        // instead of filling two or three of them.
         if (tid > 0 && tid < 8) {
             const int c = p.cus_per_xcd;
-            res = (res + c / 2) / c * c;
-            res = res < nH ? res : nH;
+            if (nH <= 8 * c) {
+                res = (tid * nH) >> 3;
+            } else {
+                res = (res + c / 2) / c * c;
+                res = res < nH ? res : nH;
+            }
         }
         s_ts[tid] = res;
         s_sl[tid] = (int)(((long long)tid * nL) >> 3);
