@@ -1,6 +1,6 @@
 """Turn the raw rocprofv3 output of ONE profiling session into the short summaries under profiles/.
 
-A session is a directory (kept under gpurun_out/, never committed) with these sub-directories, each written by
+A session is a scratch directory (raw profiler output, never committed) with these sub-directories, each written by
 one rocprofv3 run of the committed bench.py (the commands are repeated at the top of the summary this writes):
 
     kt/     --kernel-trace --stats                       kt_kernel_stats.csv, bench.log   (the only one required)
@@ -83,7 +83,7 @@ def main() -> int:
     L = []
     L.append("# rocprofv3 summaries: whole layer step, workload %s\n" % wl_args)
     L.append("Measured at commit %s; every section comes from one run of the committed bench.py, all runs in one session on one box." % args.commit)
-    L.append("Commands (from /tmp with TMPDIR=/tmp; R = repository root, S = the session's output directory under gpurun_out/):\n")
+    L.append("Commands (from /tmp with TMPDIR=/tmp; R = repository root, S = the session's scratch output directory):\n")
     L.append("    export MOE_TED_SERIAL=1   # kernel trace only: every GEMM on the caller's stream, so durations are those of kernels that have the chip to themselves")
     L.append("    rocprofv3 --kernel-trace --stats -d $S/kt -o kt --output-format csv -- python3 $R/bench.py --workload %s --steps 10 --warmup 3 --no-cpu-baseline --no-isolated" % wl_args)
     L.append("    unset MOE_TED_SERIAL")
