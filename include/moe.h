@@ -44,8 +44,11 @@
  *    nothing.  moe_last_error() gives a thread-local description.
  *  - Not checked (undefined results, no memory fault as long as the arrays have
  *    the stated sizes and expert/slot came from moe_gate): non-finite logits.
- *  - Limits: 1 <= E <= 256; h and f multiples of 8 (bf16) or 4 (fp32);
- *    T, C >= 1; E*C*max(h,f) < 2^40; C*max(h,f)*sizeof(dtype) < 2^31.
+ *  - Limits: 1 <= E <= 256; h and f multiples of 8 (bf16) or 4 (fp32), at most
+ *    2^20; 1 <= T, C < 2^31; T*h*sizeof(dtype) < 2^37; E*C*max(h,f) < 2^40;
+ *    C*max(h,f)*sizeof(dtype) < 2^31 and h*f*sizeof(dtype) < 2^31 (one expert's
+ *    chunk and one expert's weight matrix are addressed through 32-bit
+ *    windows; whole tensors may be larger than 4 GiB).
  */
 #ifndef MOE_TED_H
 #define MOE_TED_H

@@ -613,7 +613,10 @@ template <int CW, int EJ>
 static void launch_dx(const moe_shape_t *sh, const float *w_gate, const float *d_logits, void *d_x, int j0,
                       hipStream_t s, const void *d_buf = nullptr, const int32_t *expert = nullptr,
                       const int32_t *slot = nullptr, int tp_size = 1) {
-    const int64_t chunk_len = 64;
+    // chunks of 64 tokens, longer ones (a multiple of 64) when there would be more chunks than a grid's second
+    // dimension takes
+    int64_t chunk_len = 64;
+    while ((sh->T + chunk_len - 1) / chunk_len > 65535) chunk_len *= 2;
     dim3 grid((unsigned)((sh->h + 256 * CW - 1) / (256 * CW)), (unsigned)((sh->T + chunk_len - 1) / chunk_len));
     hipLaunchKernelGGL((gate_dx_kernel<CW, EJ>), grid, dim3(256), 0, s, w_gate, d_logits, (bf16_t *)d_x, sh->T, sh->h,
                        sh->E, j0, chunk_len, (const bf16_t *)d_buf, expert, slot, (sh->C + tp_size - 1) / tp_size, tp_size);
@@ -623,7 +626,8 @@ static void launch_dx(const moe_shape_t *sh, const float *w_gate, const float *d
 // (and moves rows through buffer resources whose offsets must stay below 2^31)
 static bool dx_rows_ok(const moe_shape_t *sh, int tp_size = 1) {
     const double src_rows = (double)tp_size * sh->E * (double)((sh->C + tp_size - 1) / tp_size);
-    return sh->E <= 64 && src_rows * sh->h * 2.0 < 2147483648.0 && (double)sh->T * sh->h * 2.0 < 2147483648.0;
+    return sh->E <= 64 && src_rows * sh->h * 2.0 < 2147483648.0 && (double)sh->T * sh->h * 2.0 < 2147483648.0 &&
+           (sh->T + DX_TOKENS - 1) / DX_TOKENS <= 65535;      // one workgroup row per DX_TOKENS tokens in the grid's second dimension
 }
 
 static void launch_dx_mfma(const moe_shape_t *sh, const float *w_gate, const float *d_logits, void *d_x, hipStream_t s,

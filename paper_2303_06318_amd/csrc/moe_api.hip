@@ -84,7 +84,10 @@ static moe_status_t check_shape(const moe_shape_t *sh) {
         return MOE_ERR_UNSUPPORTED;
     }
     const int64_t w = sh->h > sh->f ? sh->h : sh->f;
-    if (sh->T > (int64_t)0x7fffffff || sh->C > (int64_t)0x7fffffff ||
+    // (T*h*esize < 2^37: the gate backward walks x in at most 64 chunks, each through a 2 GiB buffer window;
+    // h, f <= 2^20: the gate's three bf16 planes of up to 256 expert rows stay inside such a window as well)
+    if (sh->T > (int64_t)0x7fffffff || sh->C > (int64_t)0x7fffffff || w > (1 << 20) ||
+        (double)sh->T * (double)sh->h * (double)esize(sh) >= 137438953472.0 ||
         (double)sh->E * (double)sh->C * (double)w >= 1099511627776.0 ||
         (double)sh->C * (double)w * (double)esize(sh) >= 2147483648.0 ||
         (double)sh->h * (double)sh->f * (double)esize(sh) >= 2147483648.0) {

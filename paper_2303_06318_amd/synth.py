@@ -117,6 +117,13 @@ def _token_tensor(seed, tensor_id, T, h, std, threads):
     return np.concatenate(parts, axis=0) if parts else np.zeros((0, h), np.float32)
 
 
+def token_blocks(seed: int, tensor_id: int, T: int, h: int, std: float):
+    """The blocks of rows that _token_tensor concatenates, one at a time as (first row, fp32 block): for
+    token tensors too large to hold twice on the host."""
+    for c in range((T + _ROW_BLOCK - 1) // _ROW_BLOCK):
+        yield c * _ROW_BLOCK, _draw(seed, tensor_id, c, (min(_ROW_BLOCK, T - c * _ROW_BLOCK), h), std)
+
+
 @dataclass
 class LayerInputs:
     wl: Workload

@@ -49,6 +49,12 @@ def test_capacity_and_workspace_are_pure_host_functions():
     (dict(E=257), moe.MOE_ERR_UNSUPPORTED),
     (dict(dtype=7), moe.MOE_ERR_UNSUPPORTED),
     (dict(act=9), moe.MOE_ERR_UNSUPPORTED),
+    # beyond the 32-bit windows the kernels address through: a token tensor of 2^37 bytes, a row of 2^21 elements,
+    # an expert chunk of 2 GiB, an expert weight matrix of 2 GiB
+    (dict(T=1 << 24, h=4096), moe.MOE_ERR_UNSUPPORTED),
+    (dict(h=1 << 21, f=8), moe.MOE_ERR_UNSUPPORTED),
+    (dict(Cap=1 << 22, h=256), moe.MOE_ERR_UNSUPPORTED),
+    (dict(h=32768, f=32768), moe.MOE_ERR_UNSUPPORTED),
 ])
 def test_bad_shapes_are_rejected_without_launch(kw, status):
     base = dict(T=1024, h=512, E=8, f=512, Cap=128, dtype=moe.MOE_BF16, act=moe.MOE_GELU_ERF)
