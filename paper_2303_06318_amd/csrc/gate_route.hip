@@ -257,6 +257,7 @@ __global__ __launch_bounds__(256) void gate_softmax_top1_kernel(const float *log
 
 // ------------------------------------------------------------------ routing
 constexpr int RB = 1024;   // tokens per routing block
+constexpr unsigned ROUTE_DIRECT_BLOCKS = 64;   // up to this many routing blocks, each sums the histograms in front of it itself
 
 __global__ __launch_bounds__(RB) void route_hist_kernel(const int32_t *expert, int32_t *hist, int32_t *token_of_slot,
                                                          int64_t T, int E, int64_t EC) {
@@ -271,10 +272,48 @@ __global__ __launch_bounds__(RB) void route_hist_kernel(const int32_t *expert, i
     for (int64_t i = (int64_t)blockIdx.x * RB + tid; i < EC; i += (int64_t)gridDim.x * RB) token_of_slot[i] = -1;
 }
 
-// hist holds one row of E counts per `hist_block` tokens (RB is a multiple of hist_block).
+// Many routing blocks (long token tensors): the tokens in front of every routing block, per expert, by one
+// pass over the histogram rows instead of every block summing all rows in front of it.  Workgroup e walks the
+// routing blocks 1024 at a time: a thread adds up the rows of one block, the workgroup scans the totals
+// (wave shuffles, then the 16 wave totals), and the running sum carries over to the next 1024 blocks.
+// block_base[b * E + e] = tokens of expert e in routing blocks 0 .. b-1.
+__global__ __launch_bounds__(1024) void route_block_base_kernel(const int32_t *hist, int32_t *block_base, int64_t n_rows,
+                                                                 int64_t n_blocks, int E, int rows_per_block) {
+    __shared__ int32_t wsum[16];
+    __shared__ int32_t carry_s;
+    const int e = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) carry_s = 0;
+    __syncthreads();
+    for (int64_t b0 = 0; b0 < n_blocks; b0 += 1024) {
+        const int64_t b = b0 + tid;
+        int32_t tot = 0;
+        if (b < n_blocks) {
+            const int64_t r0 = b * rows_per_block;
+            for (int r = 0; r < rows_per_block && r0 + r < n_rows; ++r) tot += hist[(r0 + r) * E + e];
+        }
+        int32_t inc = tot;                           // inclusive scan inside the wave
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int32_t v = __shfl_up(inc, o);
+            if (lane >= o) inc += v;
+        }
+        if (lane == 63) wsum[wave] = inc;
+        __syncthreads();
+        int32_t before = carry_s;                    // the carry and the waves in front of this one
+        for (int w = 0; w < wave; ++w) before += wsum[w];
+        if (b < n_blocks) block_base[b * E + e] = before + inc - tot;
+        __syncthreads();
+        if (tid == 1023) carry_s = before + inc;
+        __syncthreads();
+    }
+}
+
+// hist holds one row of E counts per `hist_block` tokens (RB is a multiple of hist_block).  block_base: the
+// result of route_block_base_kernel, or null (few routing blocks: every block sums the rows in front of it).
 __global__ __launch_bounds__(RB) void route_slot_kernel(const int32_t *expert, const int32_t *hist, int32_t *slot,
                                                          int32_t *counts, int32_t *kept, int32_t *token_of_slot,
-                                                         int64_t T, int E, int64_t C, int hist_block) {
+                                                         int64_t T, int E, int64_t C, int hist_block,
+                                                         const int32_t *block_base) {
     __shared__ int32_t base[256];
     __shared__ int32_t wcnt[RB / 64][256];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -284,10 +323,14 @@ __global__ __launch_bounds__(RB) void route_slot_kernel(const int32_t *expert, c
     __syncthreads();
     // tokens before this block: all histogram rows in front of it, summed by all threads at once
     // (consecutive threads read consecutive counts; integer atomics, so the order does not matter)
-    const int64_t n_before = (int64_t)b * (RB / hist_block) * E;
-    for (int64_t i = tid; i < n_before; i += RB) {
-        const int32_t v = hist[i];
-        if (v) atomicAdd(&base[(int)(i % E)], v);
+    if (block_base != nullptr) {
+        if (tid < E) base[tid] = block_base[(int64_t)b * E + tid];
+    } else {
+        const int64_t n_before = (int64_t)b * (RB / hist_block) * E;
+        for (int64_t i = tid; i < n_before; i += RB) {
+            const int32_t v = hist[i];
+            if (v) atomicAdd(&base[(int)(i % E)], v);
+        }
     }
     __syncthreads();
     const int64_t t = (int64_t)b * RB + tid;
@@ -335,7 +378,8 @@ size_t gate_ws_bytes(const moe_shape_t *sh) {
     while (NT * 16 < sh->E) NT *= 2;
     size_t planes = (size_t)3 * NT * 16 * sh->h * 2;
     size_t hist = (size_t)((sh->T + 15) / 16) * sh->E * 4;        // one row per 16 tokens at most (see run_gate)
-    return ((planes + 255) / 256) * 256 + ((hist + 255) / 256) * 256;
+    size_t bases = (size_t)((sh->T + RB - 1) / RB) * sh->E * 4;   // tokens in front of every routing block
+    return ((planes + 255) / 256) * 256 + ((hist + 255) / 256) * 256 + ((bases + 255) / 256) * 256;
 }
 
 template <int NT, int R, int NW, int U>
@@ -389,8 +433,16 @@ moe_status_t run_gate(const moe_shape_t *sh, const void *x, const float *w_gate,
         hipLaunchKernelGGL(route_hist_kernel, dim3(nb), dim3(RB), 0, s, expert, hist, token_of_slot, T, sh->E,
                            (int64_t)sh->E * sh->C);
     }
+    // beyond ROUTE_DIRECT_BLOCKS routing blocks one more small kernel sums the histograms once for all
+    int32_t *block_base = nullptr;
+    if (nb > ROUTE_DIRECT_BLOCKS) {
+        const size_t hist_bytes = (((size_t)((T + 15) / 16) * sh->E * 4 + 255) / 256) * 256;
+        block_base = (int32_t *)((char *)hist + hist_bytes);
+        hipLaunchKernelGGL(route_block_base_kernel, dim3((unsigned)sh->E), dim3(1024), 0, s, hist, block_base,
+                           (T + hist_block - 1) / hist_block, (int64_t)nb, sh->E, RB / hist_block);
+    }
     hipLaunchKernelGGL(route_slot_kernel, dim3(nb), dim3(RB), 0, s, expert, hist, slot, counts, kept, token_of_slot,
-                       T, sh->E, sh->C, hist_block);
+                       T, sh->E, sh->C, hist_block, block_base);
     return check_launch("route");
 }
 

@@ -158,7 +158,10 @@ def route_only(orc, logits, E, cf, Cap=None):
 
 
 @pytest.mark.parametrize("T,E,cf", [(1, 1, 1.0), (63, 3, 1.0), (1000, 7, 0.5), (1024, 16, 1.25), (1025, 64, 1.0),
-                                     (5000, 256, 1.0), (16384, 16, 1.25), (16384, 64, 1.0), (40000, 33, 0.3)])
+                                     (5000, 256, 1.0), (16384, 16, 1.25), (16384, 64, 1.0), (40000, 33, 0.3),
+                                     # more than 64 routing blocks of 1024 tokens: the histograms are summed once
+                                     # for all blocks by a kernel of their own (65537: 65 blocks, the last of 1 token)
+                                     (65537, 5, 1.0), (300001, 256, 0.7), (2100000, 9, 1.25)])
 def test_routing_given_oracle_logits(orc, T, E, cf):
     rng = np.random.default_rng(T + E)
     logits = rng.standard_normal((T, E)).astype(np.float32)
