@@ -14,7 +14,7 @@ from paper_2303_06318_amd import moe, synth
 from paper_2303_06318_amd.layer import MoeLayer
 from gpu_util import relfro
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
 T, H, E, F = 540_000, 4096, 8, 8
 CAPACITY_FACTOR = 1.0
