@@ -144,8 +144,11 @@ def main() -> int:
         L.append("\n## 2. HBM traffic per launch (FETCH_SIZE / WRITE_SIZE in KiB per dispatch, two runs)\n")
         L.append("Calibration: the plain 1 GiB device copy reads FETCH_SIZE = %.0f KiB and WRITE_SIZE = %.0f KiB for 1048576 KiB "
                  "each way, so the counters are scaled by %.3f (fetch) and %.3f (write).\n" % (cf or 0, cw or 0, sf, sw))
-        L.append("| kernel | dispatches | FETCH_SIZE KiB | WRITE_SIZE KiB | scaled HBM bytes per launch |")
-        L.append("|---|---|---|---|---|")
+        L.append("Last two columns: the kernel's average duration in the kernel trace of section 1 and the counter bytes "
+                 "over that duration (as a fraction of 8 TB/s).\n")
+        L.append("| kernel | dispatches | FETCH_SIZE KiB | WRITE_SIZE KiB | scaled HBM bytes per launch | avg us | counter GB/s |")
+        L.append("|---|---|---|---|---|---|---|")
+        dur = {r["Name"]: float(r["AverageNs"]) / 1e3 for r in stats}
         tot_bytes = tot_n = 0
         for k in sorted(F, key=lambda k: -mean(F[k].get("FETCH_SIZE", [0]))):
             if "copyBuffer" in k or "FETCH_SIZE" not in F[k] or k not in W:
@@ -153,7 +156,10 @@ def main() -> int:
             f, w = mean(F[k]["FETCH_SIZE"]), mean(W[k]["WRITE_SIZE"])
             by = (f * sf + w * sw) * 1024.0
             label = GEMM_NAMES.get(gemm_key(k) or "", None)
-            L.append("| `%s`%s | %d | %.0f | %.0f | %.3f GB |" % (k[:70], " -- " + label if label else "", len(F[k]["FETCH_SIZE"]), f, w, by / 1e9))
+            us = dur.get(k)
+            rate = "%.1f | %.0f (%.2f)" % (us, by / us / 1e3, by / us / 1e3 / 8000.0) if us else " | "
+            L.append("| `%s`%s | %d | %.0f | %.0f | %.3f GB | %s |" % (k[:70], " -- " + label if label else "", len(F[k]["FETCH_SIZE"]), f, w,
+                                                                   by / 1e9, rate))
             if "gemm_bf16_kernel" in k:
                 n = len(F[k]["FETCH_SIZE"])
                 tot_bytes += by * n
