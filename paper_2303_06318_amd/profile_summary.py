@@ -69,17 +69,18 @@ def gemm_key(name):
     return None
 
 
-def main() -> int:
+def main(argv=None) -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("session")
     ap.add_argument("--workload", required=True)
     ap.add_argument("--commit", required=True, help="the commit the profiled tree was built from")
     ap.add_argument("--out", default=None, help="summary file name under profiles/ (default: layer_<workload>.md)")
+    ap.add_argument("--profiles-dir", default=os.path.join(ROOT, "profiles"), help="where the summaries are written")
     ap.add_argument("--bench-args", default="", help="further bench.py arguments the session's runs were made with (e.g. --fused)")
-    args = ap.parse_args()
+    args = ap.parse_args(argv)
     S = args.session
     wl_args = args.workload + (" " + args.bench_args.strip() if args.bench_args.strip() else "")
-    out_md = os.path.join(ROOT, "profiles", args.out or "layer_%s.md" % args.workload)
+    out_md = os.path.join(args.profiles_dir, args.out or "layer_%s.md" % args.workload)
     L = []
     L.append("# rocprofv3 summaries: whole layer step, workload %s\n" % wl_args)
     L.append("Measured at commit %s; every section comes from one run of the committed bench.py, all runs in one session on one box." % args.commit)
@@ -184,7 +185,7 @@ def main() -> int:
     print("wrote", out_md)
 
     if traffic_avg is not None:
-        tpath = os.path.join(ROOT, "profiles", "gemm_traffic.txt")
+        tpath = os.path.join(args.profiles_dir, "gemm_traffic.txt")
         lines = []
         if os.path.exists(tpath):
             lines = [l.rstrip("\n") for l in open(tpath) if not (l.strip() and not l.startswith("#") and ("workload=%s " % args.workload) in l + " ")]
