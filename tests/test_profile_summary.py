@@ -47,3 +47,15 @@ def test_summary_tables_and_traffic_line(tmp_path):
     assert "workload=other bytes_per_launch=1 commit=x summary=y" in lines          # other workloads' lines stay
     assert not any("commit=old" in l for l in lines)                                    # this workload's line is replaced
     assert "workload=wl bytes_per_launch=%d commit=abc1234 summary=layer_wl.md" % want in lines
+
+
+def test_bench_reads_the_committed_traffic_line():
+    """bench.py takes roofline.traffic from the committed profiles/gemm_traffic.txt: the headline workload has a line,
+    with the commit it was measured at, and the figure lies between the algorithmic bytes of a launch and three
+    times as much; a workload without a line gives None (the field is then null)."""
+    import bench
+    v, commit = bench.measured_gemm_traffic("cfg5_6p7b_tp4_fwdbwd")
+    assert commit and len(commit) >= 7
+    algorithmic = 16 * 4096 * 4096 * 2 + 16384 * (4096 + 4096) * 2
+    assert algorithmic <= v <= 3 * algorithmic
+    assert bench.measured_gemm_traffic("no_such_workload") == (None, None)
